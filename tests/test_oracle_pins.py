@@ -1,0 +1,447 @@
+"""Pins of the fp64 oracle against things other than itself: a hand-worked
+example, closed forms, invariants, brute force, finite differences and an
+independent library routine.  CPU only."""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import burst_oracle as oc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def rand_qkvdo(seed, nq, nk, d):
+    r = rng(seed)
+    return (r.standard_normal((nq, d)), r.standard_normal((nk, d)),
+            r.standard_normal((nk, d)), r.standard_normal((nq, d)))
+
+
+# ----------------------------------------------------------------- worked example
+
+def load_golden(name):
+    vals = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            k, v = line.split()
+            vals[k] = float(v)
+    return vals
+
+
+def test_hand_worked_two_key_example():
+    g = load_golden("softmax_two_keys.txt")
+    Q = np.array([[1.0]])
+    K = np.array([[0.0], [math.log(3.0)]])
+    V = np.array([[0.0], [4.0]])
+    dO = np.array([[1.0]])
+    O, lse = oc.attention_fwd(Q, K, V, 1.0)
+    assert lse[0] == pytest.approx(g["lse"], abs=1e-15)
+    assert O[0, 0] == pytest.approx(g["o"], abs=1e-14)
+    P = oc.attention_probs(Q, K, 1.0)
+    assert P[0] == pytest.approx([g["p0"], g["p1"]], abs=1e-15)
+    # the step formulation and the two-step merge
+    O2, lse2 = oc.step_fwd(Q, K, V, 1.0)
+    assert O2[0, 0] == pytest.approx(g["o"], abs=1e-14) and lse2[0] == pytest.approx(g["lse"], abs=1e-15)
+    Oa, la = oc.step_fwd(Q, K[:1], V[:1], 1.0)
+    Ob, lb = oc.step_fwd(Q, K[1:], V[1:], 1.0)
+    Om, lm = oc.lse_merge(*oc.lse_merge(np.zeros((1, 1)), np.full(1, -np.inf), Oa, la), Ob, lb)
+    assert Om[0, 0] == pytest.approx(g["o"], abs=1e-14) and lm[0] == pytest.approx(g["lse"], abs=1e-15)
+    # backward
+    D = oc.preprocess_bwd(dO, O)
+    assert D[0] == pytest.approx(g["D"], abs=1e-14)
+    dQ, dK, dV = oc.step_bwd(Q, K, V, dO, lse, D, 1.0)
+    assert dQ[0, 0] == pytest.approx(g["dq"], abs=1e-14)
+    assert dK[:, 0] == pytest.approx([g["dk0"], g["dk1"]], abs=1e-14)
+    assert dV[:, 0] == pytest.approx([g["dv0"], g["dv1"]], abs=1e-14)
+    dQ2, dK2, dV2 = oc.attention_bwd(Q, K, V, dO, 1.0)
+    assert dQ2[0, 0] == pytest.approx(g["dq"], abs=1e-14)
+    assert dK2[:, 0] == pytest.approx([g["dk0"], g["dk1"]], abs=1e-14)
+
+
+# ----------------------------------------------------------------- softmax / closed forms
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_probability_rows_sum_to_one(causal):
+    Q, K, V, _ = rand_qkvdo(1, 37, 37, 8)
+    vis = oc.visibility(np.arange(37), np.arange(37), causal)
+    P = oc.attention_probs(Q, K, 0.35, vis)
+    assert np.abs(P.sum(axis=1) - 1.0).max() < 1e-12
+    assert (P[~vis] == 0).all()
+
+
+def test_equal_keys_give_uniform_attention():
+    r = rng(2)
+    nq, nk, d, scale = 9, 13, 6, 0.4
+    Q = r.standard_normal((nq, d))
+    krow = r.standard_normal(d)
+    K = np.tile(krow, (nk, 1))
+    V = r.standard_normal((nk, d))
+    pos_q = np.arange(4, 4 + nq)
+    pos_k = np.arange(nk)
+    vis = oc.visibility(pos_q, pos_k, True)
+    O, lse = oc.attention_fwd(Q, K, V, scale, vis)
+    for rr in range(nq):
+        n = int(vis[rr].sum())
+        assert O[rr] == pytest.approx(V[:n].mean(axis=0), abs=1e-13)
+        assert lse[rr] == pytest.approx(scale * Q[rr] @ krow + math.log(n), abs=1e-13)
+
+
+def test_single_visible_key_copies_value():
+    Q, K, V, _ = rand_qkvdo(3, 5, 5, 4)
+    vis = np.eye(5, dtype=bool)
+    O, lse = oc.attention_fwd(Q, K, V, 0.5, vis)
+    assert O == pytest.approx(V, abs=1e-14)
+    assert lse == pytest.approx(0.5 * (Q * K).sum(axis=1), abs=1e-14)
+
+
+def test_key_shift_invariance():
+    Q, K, V, _ = rand_qkvdo(4, 11, 17, 8)
+    c = rng(5).standard_normal(8)
+    O1, l1 = oc.attention_fwd(Q, K, V, 0.3)
+    O2, l2 = oc.attention_fwd(Q, K + c, V, 0.3)
+    assert O2 == pytest.approx(O1, abs=1e-12)
+    assert l2 - l1 == pytest.approx(0.3 * Q @ c, abs=1e-12)
+
+
+def test_scale_is_applied_to_scores():
+    # a transposed operand or a dropped scale changes this closed form
+    Q = np.array([[2.0, 0.0]])
+    K = np.array([[1.0, 5.0], [3.0, -7.0]])
+    V = np.array([[1.0, 0.0], [0.0, 1.0]])
+    O, lse = oc.attention_fwd(Q, K, V, 0.5)
+    # S = 0.5 * (2, 6) = (1, 3)
+    z = math.exp(1.0) + math.exp(3.0)
+    assert lse[0] == pytest.approx(math.log(z), abs=1e-14)
+    assert O[0] == pytest.approx([math.exp(1.0) / z, math.exp(3.0) / z], abs=1e-14)
+
+
+def test_all_masked_row_is_zero_and_minus_inf():
+    Q, K, V, _ = rand_qkvdo(6, 4, 6, 3)
+    vis = np.ones((4, 6), dtype=bool)
+    vis[2] = False
+    O, lse = oc.step_fwd(Q, K, V, 1.0, vis)
+    assert (O[2] == 0).all() and lse[2] == -np.inf
+    assert np.isfinite(lse[[0, 1, 3]]).all()
+    O2, lse2 = oc.attention_fwd(Q, K, V, 1.0, vis)
+    assert (O2[2] == 0).all() and lse2[2] == -np.inf
+
+
+# ----------------------------------------------------------------- merge
+
+def test_merge_identity_and_self_merge():
+    Q, K, V, _ = rand_qkvdo(7, 6, 9, 4)
+    O, lse = oc.step_fwd(Q, K, V, 0.5)
+    zero, ninf = np.zeros_like(O), np.full(6, -np.inf)
+    O1, l1 = oc.lse_merge(zero, ninf, O, lse)
+    assert (O1 == O).all() and (l1 == lse).all()
+    O2, l2 = oc.lse_merge(O, lse, zero, ninf)
+    assert (O2 == O).all() and (l2 == lse).all()
+    O3, l3 = oc.lse_merge(zero, ninf, zero, ninf)
+    assert (O3 == 0).all() and (l3 == -np.inf).all()
+    O4, l4 = oc.lse_merge(O, lse, O, lse)
+    assert O4 == pytest.approx(O, abs=1e-14)
+    assert l4 == pytest.approx(lse + math.log(2.0), abs=1e-14)
+
+
+def test_merge_weights_hand_values():
+    # lse_i = ln 1, lse_cur = ln 3  ->  weights 1/4 and 3/4
+    O, l = oc.lse_merge(np.array([[8.0]]), np.array([0.0]), np.array([[4.0]]), np.array([math.log(3.0)]))
+    assert l[0] == pytest.approx(math.log(4.0), abs=1e-15)
+    assert O[0, 0] == pytest.approx(0.25 * 8.0 + 0.75 * 4.0, abs=1e-14)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("G", [1, 2, 4])
+def test_ring_merge_equals_unsharded_any_order(causal, G):
+    N, d, scale = 48, 8, 0.3
+    Q, K, V, _ = rand_qkvdo(8 + G, N, N, d)
+    pos = [oc.contiguous_positions(i, G, N) for i in range(G)]
+    O_ref, lse_ref = oc.attention_fwd(Q, K, V, scale, oc.visibility(np.arange(N), np.arange(N), causal))
+    Ks = [K[p] for p in pos]
+    Vs = [V[p] for p in pos]
+    for i in range(G):
+        orders = [oc.ring_order(i, G), oc.ring_order(i, G, reverse=True)]
+        if G == 4:
+            orders += [list(p) for p in itertools.islice(itertools.permutations(range(G)), 5, 24, 7)]
+        for order in orders:
+            O, lse = oc.ring_fwd(Q[pos[i]], Ks, Vs, scale,
+                                 lambda j: oc.visibility(pos[i], pos[j], causal), order)
+            assert np.abs(O - O_ref[pos[i]]).max() < 1e-12
+            assert np.abs(lse - lse_ref[pos[i]]).max() < 1e-12
+
+
+# ----------------------------------------------------------------- partitions and masks
+
+@pytest.mark.parametrize("G,N", [(1, 6), (2, 12), (3, 30), (4, 40)])
+def test_partitions_cover_sequence_once(G, N):
+    for fn in (oc.contiguous_positions, oc.zigzag_positions, oc.striped_positions):
+        allpos = np.concatenate([fn(i, G, N) for i in range(G)])
+        assert sorted(allpos.tolist()) == list(range(N))
+        assert all(fn(i, G, N).size == N // G for i in range(G))
+
+
+def test_zigzag_positions_match_equation_one_based():
+    # Eq. 11 literally, 1-based tokens x_1..x_n: front k in [(i-1)P+1, iP],
+    # back k in [n-iP+1, n-(i-1)P]
+    G, N = 4, 40
+    P = N // (2 * G)
+    for i1 in range(1, G + 1):
+        front = list(range((i1 - 1) * P + 1, i1 * P + 1))
+        back = list(range(N - i1 * P + 1, N - (i1 - 1) * P + 1))
+        expect = [k - 1 for k in front + back]
+        assert oc.zigzag_positions(i1 - 1, G, N).tolist() == expect
+
+
+def causal_brute(pos_q, pos_k):
+    return np.array([[pq >= pk for pk in pos_k] for pq in pos_q], dtype=bool)
+
+
+@pytest.mark.parametrize("G,N", [(2, 12), (3, 30), (4, 40)])
+def test_zigzag_case_table_equals_position_predicate_and_global_causal(G, N):
+    d, scale = 4, 0.6
+    Q, K, V, _ = rand_qkvdo(20 + G, N, N, d)
+    P = N // (2 * G)
+    O_ref, lse_ref = oc.attention_fwd(Q, K, V, scale, causal_brute(range(N), range(N)))
+    pos = [oc.zigzag_positions(i, G, N) for i in range(G)]
+    total_pairs = 0
+    for i in range(G):
+        O_acc, lse_acc = np.zeros((2 * P, d)), np.full(2 * P, -np.inf)
+        for j in oc.ring_order(i, G):
+            vis = oc.visibility(pos[i], pos[j], True)
+            assert (vis == causal_brute(pos[i], pos[j])).all()
+            n_pairs = int(vis.sum())
+            assert n_pairs == (2 * P * P + P if i == j else 2 * P * P)
+            assert n_pairs == oc.visible_pairs(pos[i], pos[j], True)
+            total_pairs += n_pairs
+            O_pos, lse_pos = oc.step_fwd(Q[pos[i]], K[pos[j]], V[pos[j]], scale, vis)
+            O_case, lse_case = oc.zigzag_step_fwd_cases(i, j, Q[pos[i]], K[pos[j]], V[pos[j]], scale)
+            assert np.abs(O_pos - O_case).max() < 1e-13
+            with np.errstate(invalid="ignore"):
+                assert ((lse_pos == lse_case) | (np.abs(lse_pos - lse_case) < 1e-13)).all()
+            O_acc, lse_acc = oc.lse_merge(O_acc, lse_acc, O_case, lse_case)
+        assert np.abs(O_acc - O_ref[pos[i]]).max() < 1e-12
+        assert np.abs(lse_acc - lse_ref[pos[i]]).max() < 1e-12
+    assert total_pairs == N * (N + 1) // 2
+
+
+@pytest.mark.parametrize("G,N", [(2, 12), (4, 24)])
+def test_contiguous_and_striped_causal_steps_cover_global_causal(G, N):
+    for fn in (oc.contiguous_positions, oc.striped_positions):
+        pos = [fn(i, G, N) for i in range(G)]
+        total = sum(oc.visible_pairs(pos[i], pos[j], True) for i in range(G) for j in range(G))
+        assert total == N * (N + 1) // 2
+    # striped, Eq. 14: i >= j is plain causal on local indices, i < j drops the diagonal
+    pos = [oc.striped_positions(i, G, N) for i in range(G)]
+    n = N // G
+    for i in range(G):
+        for j in range(G):
+            vis = oc.visibility(pos[i], pos[j], True)
+            tri = np.tril(np.ones((n, n), dtype=bool), 0 if i >= j else -1)
+            assert (vis == tri).all()
+
+
+# ----------------------------------------------------------------- gradients
+
+def loss(Q, K, V, dO, scale, vis):
+    return float((oc.attention_fwd(Q, K, V, scale, vis)[0] * dO).sum())
+
+
+def fd_grad(f, X, h=1e-5):
+    G = np.zeros_like(X)
+    for idx in np.ndindex(*X.shape):
+        old = X[idx]
+        X[idx] = old + h
+        fp = f()
+        X[idx] = old - h
+        fm = f()
+        X[idx] = old
+        G[idx] = (fp - fm) / (2 * h)
+    return G
+
+
+@pytest.mark.parametrize("kind", ["full", "causal", "rect_causal"])
+def test_gradients_match_central_finite_differences(kind):
+    nq, nk, d, scale = (16, 16, 4, 0.5) if kind != "rect_causal" else (7, 12, 3, 0.7)
+    Q, K, V, dO = rand_qkvdo(30, nq, nk, d)
+    if kind == "full":
+        vis = None
+    elif kind == "causal":
+        vis = oc.visibility(np.arange(nq), np.arange(nk), True)
+    else:
+        vis = oc.visibility(np.arange(5, 5 + nq), np.arange(nk), True)
+    dQ, dK, dV = oc.attention_bwd(Q, K, V, dO, scale, vis)
+    f = lambda: loss(Q, K, V, dO, scale, vis)
+    for got, X in ((dQ, Q), (dK, K), (dV, V)):
+        ref = fd_grad(f, X)
+        assert np.abs(got - ref).max() <= 1e-7 * max(1.0, np.abs(ref).max())
+    # the step formulation with D = rowsum(dO o O) gives the same gradient
+    O, lse = oc.attention_fwd(Q, K, V, scale, vis)
+    dQ2, dK2, dV2 = oc.step_bwd(Q, K, V, dO, lse, oc.preprocess_bwd(dO, O), scale, vis)
+    for a, b in ((dQ, dQ2), (dK, dK2), (dV, dV2)):
+        assert np.abs(a - b).max() < 1e-12
+
+
+def test_backward_invariants():
+    nq, nk, d, scale = 24, 24, 8, 0.35
+    Q, K, V, dO = rand_qkvdo(31, nq, nk, d)
+    vis = oc.visibility(np.arange(nq), np.arange(nk), True)
+    O, lse = oc.attention_fwd(Q, K, V, scale, vis)
+    P = oc.attention_probs(Q, K, scale, vis)
+    dP = dO @ V.T
+    D = oc.preprocess_bwd(dO, O)
+    # Eq. 7-8: rowsum(P o dP) = rowsum(dO o O)
+    assert np.abs((P * dP).sum(axis=1) - D).max() < 1e-12
+    dS = P * (dP - D[:, None])
+    assert np.abs(dS.sum(axis=1)).max() < 1e-12
+    dQ, dK, dV = oc.attention_bwd(Q, K, V, dO, scale, vis)
+    assert np.abs(dV.sum(axis=0) - dO.sum(axis=0)).max() < 1e-12
+    # softmax is invariant to a common shift of the keys: sum_c dK[c] = 0
+    assert np.abs(dK.sum(axis=0)).max() < 1e-12
+
+
+def test_partial_lse_breaks_the_D_identity():
+    # feeding a step-partial Lse/O instead of the final ones must NOT give
+    # the right gradient (reading: backward uses the final Lse and D)
+    N, d, scale = 16, 4, 0.5
+    Q, K, V, dO = rand_qkvdo(32, N, N, d)
+    dQ_ref, _, _ = oc.attention_bwd(Q, K, V, dO, scale)
+    O_half, lse_half = oc.step_fwd(Q, K[:8], V[:8], scale)
+    dq_a, _, _ = oc.step_bwd(Q, K[:8], V[:8], dO, lse_half, oc.preprocess_bwd(dO, O_half), scale)
+    dq_b, _, _ = oc.step_bwd(Q, K[8:], V[8:], dO, lse_half, oc.preprocess_bwd(dO, O_half), scale)
+    assert np.abs(dq_a + dq_b - dQ_ref).max() > 1e-3
+
+
+@pytest.mark.parametrize("part", ["contiguous", "zigzag", "striped"])
+@pytest.mark.parametrize("causal", [False, True])
+def test_both_backward_travel_orders_equal_unsharded(part, causal):
+    G, N, d, scale = 3, 36, 4, 0.45
+    Q, K, V, dO = rand_qkvdo(40, N, N, d)
+    fn = {"contiguous": oc.contiguous_positions, "zigzag": oc.zigzag_positions,
+          "striped": oc.striped_positions}[part]
+    pos = [fn(i, G, N) for i in range(G)]
+    vis_glob = oc.visibility(np.arange(N), np.arange(N), causal)
+    O, lse = oc.attention_fwd(Q, K, V, scale, vis_glob)
+    dQ_ref, dK_ref, dV_ref = oc.attention_bwd(Q, K, V, dO, scale, vis_glob)
+    D = oc.preprocess_bwd(dO, O)
+    vis = lambda a, b: oc.visibility(pos[a], pos[b], causal)
+    Qs, dOs = [Q[p] for p in pos], [dO[p] for p in pos]
+    Ks, Vs = [K[p] for p in pos], [V[p] for p in pos]
+    lses, Ds = [lse[p] for p in pos], [D[p] for p in pos]
+    # Alg. 2: K, V stay; Q bundles travel
+    dQ2 = [np.zeros((len(p), d)) for p in pos]
+    for i in range(G):
+        dK_i, dV_i, contrib = oc.ring_bwd_burst(i, Qs, dOs, lses, Ds, Ks[i], Vs[i], scale, vis,
+                                                oc.ring_order(i, G))
+        assert np.abs(dK_i - dK_ref[pos[i]]).max() < 1e-12
+        assert np.abs(dV_i - dV_ref[pos[i]]).max() < 1e-12
+        for j, dq in contrib.items():
+            dQ2[j] += dq
+    # Alg. 1: Q stays; K, V, dK, dV travel
+    dK1 = [np.zeros((len(p), d)) for p in pos]
+    dV1 = [np.zeros((len(p), d)) for p in pos]
+    for i in range(G):
+        dQ_i, dKc, dVc = oc.ring_bwd_ring(i, Qs[i], dOs[i], O[pos[i]], lses[i], Ks, Vs, scale, vis,
+                                          oc.ring_order(i, G, reverse=True))
+        assert np.abs(dQ_i - dQ_ref[pos[i]]).max() < 1e-12
+        assert np.abs(dQ_i - dQ2[i]).max() < 1e-12
+        for j in range(G):
+            dK1[j] += dKc[j]
+            dV1[j] += dVc[j]
+    for i in range(G):
+        assert np.abs(dK1[i] - dK_ref[pos[i]]).max() < 1e-12
+        assert np.abs(dV1[i] - dV_ref[pos[i]]).max() < 1e-12
+
+
+# ----------------------------------------------------------------- multi-head / GQA
+
+def test_grouped_query_wrappers_against_per_head_loops_and_fd():
+    B, S, Hq, Hkv, d, scale = 2, 10, 4, 2, 3, 0.6
+    r = rng(50)
+    Q = r.standard_normal((B, S, Hq, d))
+    K = r.standard_normal((B, S, Hkv, d))
+    V = r.standard_normal((B, S, Hkv, d))
+    dO = r.standard_normal((B, S, Hq, d))
+    vis = oc.visibility(np.arange(S), np.arange(S), True)
+    assert [oc.kv_head_of(h, 4, 2) for h in range(4)] == [0, 0, 1, 1]
+    O, lse = oc.mha_attention_fwd(Q, K, V, scale, vis)
+    dQ, dK, dV = oc.mha_attention_bwd(Q, K, V, dO, scale, vis)
+    f = lambda: float((oc.mha_attention_fwd(Q, K, V, scale, vis)[0] * dO).sum())
+    for got, X in ((dQ, Q), (dK, K), (dV, V)):
+        ref = fd_grad(f, X)
+        assert np.abs(got - ref).max() <= 1e-7 * max(1.0, np.abs(ref).max())
+    D = oc.mha_preprocess_bwd(dO, O)
+    dQ2, dK2, dV2 = oc.mha_step_bwd(Q, K, V, dO, lse, D, scale, vis)
+    for a, b in ((dQ, dQ2), (dK, dK2), (dV, dV2)):
+        assert np.abs(a - b).max() < 1e-12
+    O2, lse2 = oc.mha_step_fwd(Q, K, V, scale, vis)
+    assert np.abs(O - O2).max() < 1e-12 and np.abs(lse - lse2).max() < 1e-12
+    Om, lm = oc.mha_lse_merge(np.zeros_like(O), np.full(lse.shape, -np.inf), O2, lse2)
+    assert (Om == O2).all() and (lm == lse2).all()
+
+
+# ----------------------------------------------------------------- independent library routine
+
+def test_against_torch_sdpa_float64_autograd():
+    torch = pytest.importorskip("torch")
+    B, S, Hq, Hkv, d = 1, 33, 4, 2, 8
+    scale = 1.0 / math.sqrt(d)
+    r = rng(60)
+    Q = r.standard_normal((B, S, Hq, d))
+    K = r.standard_normal((B, S, Hkv, d))
+    V = r.standard_normal((B, S, Hkv, d))
+    dO = r.standard_normal((B, S, Hq, d))
+    for causal in (False, True):
+        vis = oc.visibility(np.arange(S), np.arange(S), causal)
+        O, _ = oc.mha_attention_fwd(Q, K, V, scale, vis)
+        dQ, dK, dV = oc.mha_attention_bwd(Q, K, V, dO, scale, vis)
+        tq = torch.tensor(Q, dtype=torch.float64, requires_grad=True)
+        tk = torch.tensor(K, dtype=torch.float64, requires_grad=True)
+        tv = torch.tensor(V, dtype=torch.float64, requires_grad=True)
+        rep = Hq // Hkv
+        out = torch.nn.functional.scaled_dot_product_attention(
+            tq.permute(0, 2, 1, 3), tk.permute(0, 2, 1, 3).repeat_interleave(rep, dim=1),
+            tv.permute(0, 2, 1, 3).repeat_interleave(rep, dim=1), is_causal=causal)
+        out = out.permute(0, 2, 1, 3)
+        out.backward(torch.tensor(dO))
+        assert np.abs(out.detach().numpy() - O).max() < 1e-12
+        assert np.abs(tq.grad.numpy() - dQ).max() < 1e-12
+        assert np.abs(tk.grad.numpy() - dK).max() < 1e-12
+        assert np.abs(tv.grad.numpy() - dV).max() < 1e-12
+
+
+# ----------------------------------------------------------------- planted mistakes are caught
+
+def test_planted_mistakes_fail_the_pins(monkeypatch):
+    """Each plausible slip, planted in a copy of the oracle's arithmetic on
+    the CPU, must move a pinned quantity by far more than the pin's tolerance."""
+    Q, K, V, dO = rand_qkvdo(70, 12, 12, 4)
+    scale = 0.5
+    vis = oc.visibility(np.arange(12), np.arange(12), True)
+    dQ, dK, dV = oc.attention_bwd(Q, K, V, dO, scale, vis)
+    f = lambda: loss(Q, K, V, dO, scale, vis)
+    fdQ, fdK, fdV = fd_grad(f, Q), fd_grad(f, K), fd_grad(f, V)
+    P = oc.attention_probs(Q, K, scale, vis)
+    dP = dO @ V.T
+    O = P @ V
+    D = (dO * O).sum(1)
+    dS = P * (dP - D[:, None])
+    slips = {
+        "dropped scale in dQ": (dS @ K, fdQ),
+        "transposed dS in dK": (scale * (dS @ Q), fdK),
+        "sign of D": (scale * ((P * (dP + D[:, None])) @ K), fdQ),
+        "dV from P not P^T": (P @ dO, fdV),
+        "strict causal": (oc.attention_bwd(Q, K, V, dO, scale,
+                                           np.tril(np.ones((12, 12), bool), -1) | np.eye(12, dtype=bool)[:, ::-1])[0], fdQ),
+    }
+    for name, (wrong, ref) in slips.items():
+        assert np.abs(wrong - ref).max() > 1e-3, name
+    for good, ref in ((dQ, fdQ), (dK, fdK), (dV, fdV)):
+        assert np.abs(good - ref).max() < 1e-7
