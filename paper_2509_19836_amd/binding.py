@@ -1,0 +1,179 @@
+"""ctypes binding of libburstattn's C ABI (include/burst_attn.h).
+
+Argument marshalling only: every function here has the name of the C entry point
+it calls and does nothing but describe torch tensors as (pointer, strides) and
+pass the current HIP stream.  There is no fallback: if the shared library has
+not been built, importing this module raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libburstattn.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} not found: build it first (python -m paper_2509_19836_amd.build, or "
+        "__graft_entry__.build()); libburstattn has no CPU or PyTorch fallback")
+_lib = C.CDLL(LIB_PATH)
+
+BURST_OK, BURST_ERR_INVALID_ARG, BURST_ERR_UNSUPPORTED, BURST_ERR_HIP = 0, -1, -2, -3
+BURST_BF16, BURST_F32 = 0, 1
+BURST_MASK_FULL, BURST_MASK_CAUSAL = 0, 1
+BURST_ACC_DQ, BURST_ACC_DK, BURST_ACC_DV = 1, 2, 4
+
+
+class burst_shape_t(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("q_heads", C.c_int32), ("kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("sq", C.c_int64), ("sk", C.c_int64), ("scale", C.c_float)]
+
+
+class burst_tensor_t(C.Structure):
+    _fields_ = [("ptr", C.c_void_p), ("dtype", C.c_int32), ("_pad", C.c_int32),
+                ("stride_b", C.c_int64), ("stride_s", C.c_int64), ("stride_h", C.c_int64)]
+
+
+class burst_rowvec_t(C.Structure):
+    _fields_ = [("ptr", C.c_void_p), ("stride_b", C.c_int64), ("stride_h", C.c_int64)]
+
+
+class burst_mask_t(C.Structure):
+    _fields_ = [("mode", C.c_int32), ("q_nseg", C.c_int32), ("k_nseg", C.c_int32), ("_pad", C.c_int32),
+                ("q_seg_pos", C.c_int64 * 2), ("k_seg_pos", C.c_int64 * 2),
+                ("q_seg_len", C.c_int64), ("k_seg_len", C.c_int64), ("pos_stride", C.c_int64)]
+
+
+_P = C.POINTER
+_lib.burst_attn_step_fwd.restype = C.c_int
+_lib.burst_attn_step_fwd.argtypes = [_P(burst_shape_t), _P(burst_mask_t)] + [_P(burst_tensor_t)] * 3 + [
+    _P(burst_tensor_t), _P(burst_rowvec_t), _P(burst_tensor_t), _P(burst_rowvec_t), C.c_void_p]
+_lib.burst_attn_lse_merge.restype = C.c_int
+_lib.burst_attn_lse_merge.argtypes = [_P(burst_shape_t), _P(burst_tensor_t), _P(burst_rowvec_t),
+                                      _P(burst_tensor_t), _P(burst_rowvec_t), _P(burst_tensor_t), C.c_void_p]
+_lib.burst_attn_preprocess_bwd.restype = C.c_int
+_lib.burst_attn_preprocess_bwd.argtypes = [_P(burst_shape_t), _P(burst_tensor_t), _P(burst_tensor_t),
+                                           _P(burst_rowvec_t), C.c_void_p]
+_lib.burst_attn_step_bwd.restype = C.c_int
+_lib.burst_attn_step_bwd.argtypes = [_P(burst_shape_t), _P(burst_mask_t)] + [_P(burst_tensor_t)] * 4 + [
+    _P(burst_rowvec_t)] * 2 + [_P(burst_tensor_t)] * 3 + [C.c_int32, C.c_void_p]
+for _name in ("zigzag", "contiguous", "striped"):
+    _f = getattr(_lib, f"burst_attn_fill_{_name}_mask")
+    _f.restype = C.c_int
+    _f.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int32, _P(burst_mask_t)]
+_lib.burst_attn_visible_pairs.restype = C.c_int64
+_lib.burst_attn_visible_pairs.argtypes = [_P(burst_mask_t)]
+_lib.burst_attn_status_string.restype = C.c_char_p
+_lib.burst_attn_status_string.argtypes = [C.c_int]
+_lib.burst_attn_last_hip_error.restype = C.c_int
+_lib.burst_attn_version.restype = C.c_char_p
+
+EXPORTS = ["burst_attn_step_fwd", "burst_attn_lse_merge", "burst_attn_preprocess_bwd", "burst_attn_step_bwd",
+           "burst_attn_fill_zigzag_mask", "burst_attn_fill_contiguous_mask", "burst_attn_fill_striped_mask",
+           "burst_attn_visible_pairs", "burst_attn_status_string", "burst_attn_last_hip_error",
+           "burst_attn_version"]
+
+
+class BurstError(RuntimeError):
+    def __init__(self, status):
+        self.status = status
+        msg = _lib.burst_attn_status_string(status).decode()
+        if status == BURST_ERR_HIP:
+            msg += f" (hip error {_lib.burst_attn_last_hip_error()})"
+        super().__init__(f"libburstattn: {msg}")
+
+
+def _check(status):
+    if status != BURST_OK:
+        raise BurstError(status)
+
+
+def shape(batch, q_heads, kv_heads, head_dim, sq, sk, scale):
+    return burst_shape_t(batch, q_heads, kv_heads, head_dim, sq, sk, scale)
+
+
+def tensor(t):
+    """Describe a [batch, seq, heads, head_dim] torch tensor (bf16 or fp32, last dim contiguous)."""
+    if t is None:
+        return None
+    assert t.dim() == 4 and t.stride(3) == 1, "expected [batch, seq, heads, head_dim] with contiguous head_dim"
+    dt = {torch.bfloat16: BURST_BF16, torch.float32: BURST_F32}[t.dtype]
+    return burst_tensor_t(t.data_ptr(), dt, 0, t.stride(0), t.stride(1), t.stride(2))
+
+
+def rowvec(t):
+    """Describe a [batch, heads, seq] fp32 torch tensor (seq contiguous)."""
+    if t is None:
+        return None
+    assert t.dim() == 3 and t.stride(2) == 1 and t.dtype == torch.float32
+    return burst_rowvec_t(t.data_ptr(), t.stride(0), t.stride(1))
+
+
+def _ref(x):
+    return None if x is None else C.byref(x)
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    return C.c_void_p(stream)
+
+
+def burst_attn_fill_zigzag_mask(dev_i, shard_j, G, N, causal=True):
+    m = burst_mask_t()
+    _check(_lib.burst_attn_fill_zigzag_mask(dev_i, shard_j, G, N, int(causal), C.byref(m)))
+    return m
+
+
+def burst_attn_fill_contiguous_mask(dev_i, shard_j, G, N, causal=True):
+    m = burst_mask_t()
+    _check(_lib.burst_attn_fill_contiguous_mask(dev_i, shard_j, G, N, int(causal), C.byref(m)))
+    return m
+
+
+def burst_attn_fill_striped_mask(dev_i, shard_j, G, N, causal=True):
+    m = burst_mask_t()
+    _check(_lib.burst_attn_fill_striped_mask(dev_i, shard_j, G, N, int(causal), C.byref(m)))
+    return m
+
+
+def burst_attn_visible_pairs(mask):
+    return _lib.burst_attn_visible_pairs(C.byref(mask))
+
+
+def burst_attn_version():
+    return _lib.burst_attn_version().decode()
+
+
+def burst_attn_status_string(status):
+    return _lib.burst_attn_status_string(status).decode()
+
+
+def burst_attn_step_fwd(shp, mask, q, k, v, o_part=None, lse_part=None, o_acc=None, lse_acc=None, stream=None):
+    _check(_lib.burst_attn_step_fwd(C.byref(shp), _ref(mask), _ref(tensor(q)), _ref(tensor(k)), _ref(tensor(v)),
+                                    _ref(tensor(o_part)), _ref(rowvec(lse_part)), _ref(tensor(o_acc)),
+                                    _ref(rowvec(lse_acc)), _stream(stream)))
+
+
+def burst_attn_lse_merge(shp, o_acc, lse_acc, o_part, lse_part, o_out_cast=None, stream=None):
+    _check(_lib.burst_attn_lse_merge(C.byref(shp), _ref(tensor(o_acc)), _ref(rowvec(lse_acc)),
+                                     _ref(tensor(o_part)), _ref(rowvec(lse_part)), _ref(tensor(o_out_cast)),
+                                     _stream(stream)))
+
+
+def burst_attn_preprocess_bwd(shp, o, d_o, d_out, stream=None):
+    _check(_lib.burst_attn_preprocess_bwd(C.byref(shp), _ref(tensor(o)), _ref(tensor(d_o)), _ref(rowvec(d_out)),
+                                          _stream(stream)))
+
+
+def burst_attn_step_bwd(shp, mask, q, k, v, d_o, lse, d, dq=None, dk=None, dv=None, accumulate_flags=0,
+                        stream=None):
+    _check(_lib.burst_attn_step_bwd(C.byref(shp), _ref(mask), _ref(tensor(q)), _ref(tensor(k)), _ref(tensor(v)),
+                                    _ref(tensor(d_o)), _ref(rowvec(lse)), _ref(rowvec(d)), _ref(tensor(dq)),
+                                    _ref(tensor(dk)), _ref(tensor(dv)), accumulate_flags, _stream(stream)))
+
+
+def raw():
+    """The ctypes library handle, for tests that exercise the error paths with raw structs."""
+    return _lib

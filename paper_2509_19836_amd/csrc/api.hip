@@ -1,0 +1,317 @@
+// C-ABI layer of libburstattn: argument validation, host-side mask helpers and kernel dispatch.
+// Every check runs on the host before anything is enqueued.
+#include <hip/hip_runtime.h>
+#include <cmath>
+#include <cstring>
+
+#include "../../include/burst_attn.h"
+#include "kernels.hpp"
+
+using namespace burst;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e) {
+  g_last_hip_error = (int)e;
+  return BURST_ERR_HIP;
+}
+
+constexpr int64_t kMaxRows = (int64_t)1 << 30;
+constexpr int64_t kMaxPos = ((int64_t)1 << 31) - 1;
+
+int check_shape(const burst_shape_t* s) {
+  if (!s) return BURST_ERR_INVALID_ARG;
+  if (s->batch < 1 || s->q_heads < 1 || s->kv_heads < 1 || s->head_dim < 1) return BURST_ERR_INVALID_ARG;
+  if (s->q_heads % s->kv_heads != 0) return BURST_ERR_INVALID_ARG;
+  if (s->sq < 0 || s->sk < 0 || s->sq > kMaxRows || s->sk > kMaxRows) return BURST_ERR_INVALID_ARG;
+  if (!(s->scale > 0.f) || !std::isfinite(s->scale)) return BURST_ERR_INVALID_ARG;
+  if (s->head_dim != 64 && s->head_dim != 128) return BURST_ERR_UNSUPPORTED;
+  return BURST_OK;
+}
+
+int check_tensor(const burst_tensor_t* t, int want_dtype_mask /* bit0 bf16 ok, bit1 f32 ok */, TensorDev* out) {
+  if (!t || !t->ptr) return BURST_ERR_INVALID_ARG;
+  if (t->dtype != BURST_BF16 && t->dtype != BURST_F32) return BURST_ERR_INVALID_ARG;
+  if (!((want_dtype_mask >> t->dtype) & 1)) return BURST_ERR_UNSUPPORTED;
+  if (((uintptr_t)t->ptr) & 15) return BURST_ERR_INVALID_ARG;
+  const int64_t unit = (t->dtype == BURST_BF16) ? 8 : 4;
+  if (t->stride_b % unit || t->stride_s % unit || t->stride_h % unit) return BURST_ERR_INVALID_ARG;
+  if (t->stride_b < 0 || t->stride_s < 0 || t->stride_h < 0) return BURST_ERR_INVALID_ARG;
+  out->ptr = t->ptr;
+  out->sb = t->stride_b;
+  out->ss = t->stride_s;
+  out->sh = t->stride_h;
+  out->is_f32 = (t->dtype == BURST_F32);
+  return BURST_OK;
+}
+
+int check_rowvec(const burst_rowvec_t* t, RowvecDev* out) {
+  if (!t || !t->ptr) return BURST_ERR_INVALID_ARG;
+  if (((uintptr_t)t->ptr) & 3) return BURST_ERR_INVALID_ARG;
+  if (t->stride_b < 0 || t->stride_h < 0) return BURST_ERR_INVALID_ARG;
+  out->ptr = t->ptr;
+  out->sb = t->stride_b;
+  out->sh = t->stride_h;
+  return BURST_OK;
+}
+
+int check_mask(const burst_mask_t* m, int64_t sq, int64_t sk, MaskDev* out) {
+  std::memset(out, 0, sizeof(*out));
+  if (!m) {  // no mask given: everything visible
+    out->causal = 0;
+    out->q_nseg = out->k_nseg = 1;
+    out->q_seg_len = (int32_t)sq;
+    out->k_seg_len = (int32_t)sk;
+    out->pos_stride = 1;
+    return BURST_OK;
+  }
+  if (m->mode != BURST_MASK_FULL && m->mode != BURST_MASK_CAUSAL) return BURST_ERR_INVALID_ARG;
+  if (m->q_nseg < 1 || m->q_nseg > 2 || m->k_nseg < 1 || m->k_nseg > 2) return BURST_ERR_INVALID_ARG;
+  if (m->q_seg_len < 0 || m->k_seg_len < 0 || m->pos_stride < 1) return BURST_ERR_INVALID_ARG;
+  if (m->q_seg_len * m->q_nseg != sq || m->k_seg_len * m->k_nseg != sk) return BURST_ERR_INVALID_ARG;
+  for (int s = 0; s < 2; ++s) {
+    if (s < m->q_nseg) {
+      if (m->q_seg_pos[s] < 0) return BURST_ERR_INVALID_ARG;
+      if (m->q_seg_pos[s] + m->q_seg_len * m->pos_stride > kMaxPos) return BURST_ERR_UNSUPPORTED;
+    }
+    if (s < m->k_nseg) {
+      if (m->k_seg_pos[s] < 0) return BURST_ERR_INVALID_ARG;
+      if (m->k_seg_pos[s] + m->k_seg_len * m->pos_stride > kMaxPos) return BURST_ERR_UNSUPPORTED;
+    }
+  }
+  out->causal = (m->mode == BURST_MASK_CAUSAL);
+  out->q_nseg = m->q_nseg;
+  out->k_nseg = m->k_nseg;
+  out->q_seg_len = (int32_t)m->q_seg_len;
+  out->k_seg_len = (int32_t)m->k_seg_len;
+  for (int s = 0; s < 2; ++s) {
+    out->q_seg_pos[s] = (int32_t)(s < m->q_nseg ? m->q_seg_pos[s] : 0);
+    out->k_seg_pos[s] = (int32_t)(s < m->k_nseg ? m->k_seg_pos[s] : 0);
+  }
+  out->pos_stride = (int32_t)m->pos_stride;
+  return BURST_OK;
+}
+
+#define BURST_TRY(expr)            \
+  do {                             \
+    int _st = (expr);              \
+    if (_st != BURST_OK) return _st; \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int burst_attn_step_fwd(const burst_shape_t* shape, const burst_mask_t* mask, const burst_tensor_t* q,
+                        const burst_tensor_t* k, const burst_tensor_t* v, const burst_tensor_t* o_part,
+                        const burst_rowvec_t* lse_part, const burst_tensor_t* o_acc,
+                        const burst_rowvec_t* lse_acc, void* hip_stream) {
+  BURST_TRY(check_shape(shape));
+  FwdParams p;
+  std::memset(&p, 0, sizeof(p));
+  BURST_TRY(check_mask(mask, shape->sq, shape->sk, &p.mask));
+  BURST_TRY(check_tensor(q, 1, &p.q));
+  BURST_TRY(check_tensor(k, 1, &p.k));
+  BURST_TRY(check_tensor(v, 1, &p.v));
+  const bool want_part = o_part || lse_part, want_acc = o_acc || lse_acc;
+  if (!want_part && !want_acc) return BURST_ERR_INVALID_ARG;
+  if (want_part) {
+    BURST_TRY(check_tensor(o_part, 3, &p.o_part));
+    BURST_TRY(check_rowvec(lse_part, &p.lse_part));
+  }
+  if (want_acc) {
+    BURST_TRY(check_tensor(o_acc, 2, &p.o_acc));
+    BURST_TRY(check_rowvec(lse_acc, &p.lse_acc));
+  }
+  p.batch = shape->batch;
+  p.q_heads = shape->q_heads;
+  p.kv_heads = shape->kv_heads;
+  p.head_dim = shape->head_dim;
+  p.sq = (int32_t)shape->sq;
+  p.sk = (int32_t)shape->sk;
+  p.scale = shape->scale;
+  if (p.sq == 0) return BURST_OK;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  hipError_t e;
+  if (p.sk == 0) {  // no key: the step result is (0, -inf) and the running state is unchanged
+    if (!want_part) return BURST_OK;
+    e = launch_fill_empty_fwd(p, stream);
+  } else {
+    e = launch_step_fwd(p, stream);
+  }
+  return e == hipSuccess ? BURST_OK : hip_fail(e);
+}
+
+int burst_attn_lse_merge(const burst_shape_t* shape, const burst_tensor_t* o_acc, const burst_rowvec_t* lse_acc,
+                         const burst_tensor_t* o_part, const burst_rowvec_t* lse_part,
+                         const burst_tensor_t* o_out_cast, void* hip_stream) {
+  BURST_TRY(check_shape(shape));
+  MergeParams p;
+  std::memset(&p, 0, sizeof(p));
+  BURST_TRY(check_tensor(o_acc, 2, &p.o_acc));
+  BURST_TRY(check_rowvec(lse_acc, &p.lse_acc));
+  BURST_TRY(check_tensor(o_part, 3, &p.o_part));
+  BURST_TRY(check_rowvec(lse_part, &p.lse_part));
+  if (o_out_cast) BURST_TRY(check_tensor(o_out_cast, 1, &p.o_out));
+  p.batch = shape->batch;
+  p.q_heads = shape->q_heads;
+  p.head_dim = shape->head_dim;
+  p.sq = (int32_t)shape->sq;
+  if (p.sq == 0) return BURST_OK;
+  hipError_t e = launch_lse_merge(p, (hipStream_t)hip_stream);
+  return e == hipSuccess ? BURST_OK : hip_fail(e);
+}
+
+int burst_attn_preprocess_bwd(const burst_shape_t* shape, const burst_tensor_t* o, const burst_tensor_t* d_o,
+                              const burst_rowvec_t* d_out, void* hip_stream) {
+  BURST_TRY(check_shape(shape));
+  PreParams p;
+  std::memset(&p, 0, sizeof(p));
+  BURST_TRY(check_tensor(o, 3, &p.o));
+  BURST_TRY(check_tensor(d_o, 1, &p.d_o));
+  BURST_TRY(check_rowvec(d_out, &p.d));
+  p.batch = shape->batch;
+  p.q_heads = shape->q_heads;
+  p.head_dim = shape->head_dim;
+  p.sq = (int32_t)shape->sq;
+  if (p.sq == 0) return BURST_OK;
+  hipError_t e = launch_preprocess_bwd(p, (hipStream_t)hip_stream);
+  return e == hipSuccess ? BURST_OK : hip_fail(e);
+}
+
+int burst_attn_step_bwd(const burst_shape_t* shape, const burst_mask_t* mask, const burst_tensor_t* q,
+                        const burst_tensor_t* k, const burst_tensor_t* v, const burst_tensor_t* d_o,
+                        const burst_rowvec_t* lse, const burst_rowvec_t* d, const burst_tensor_t* dq,
+                        const burst_tensor_t* dk, const burst_tensor_t* dv, int32_t accumulate_flags,
+                        void* hip_stream) {
+  BURST_TRY(check_shape(shape));
+  BwdParams p;
+  std::memset(&p, 0, sizeof(p));
+  BURST_TRY(check_mask(mask, shape->sq, shape->sk, &p.mask));
+  BURST_TRY(check_tensor(q, 1, &p.q));
+  BURST_TRY(check_tensor(k, 1, &p.k));
+  BURST_TRY(check_tensor(v, 1, &p.v));
+  BURST_TRY(check_tensor(d_o, 1, &p.d_o));
+  BURST_TRY(check_rowvec(lse, &p.lse));
+  BURST_TRY(check_rowvec(d, &p.d));
+  if (!dq && !dk && !dv) return BURST_ERR_INVALID_ARG;
+  if ((dk == nullptr) != (dv == nullptr)) return BURST_ERR_INVALID_ARG;
+  if (accumulate_flags & ~(BURST_ACC_DQ | BURST_ACC_DK | BURST_ACC_DV)) return BURST_ERR_INVALID_ARG;
+  if (dq) BURST_TRY(check_tensor(dq, 2, &p.dq));
+  if (dk) BURST_TRY(check_tensor(dk, 2, &p.dk));
+  if (dv) BURST_TRY(check_tensor(dv, 2, &p.dv));
+  p.acc_dq = (accumulate_flags & BURST_ACC_DQ) != 0;
+  p.acc_dk = (accumulate_flags & BURST_ACC_DK) != 0;
+  p.acc_dv = (accumulate_flags & BURST_ACC_DV) != 0;
+  p.batch = shape->batch;
+  p.q_heads = shape->q_heads;
+  p.kv_heads = shape->kv_heads;
+  p.head_dim = shape->head_dim;
+  p.sq = (int32_t)shape->sq;
+  p.sk = (int32_t)shape->sk;
+  p.scale = shape->scale;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  hipError_t e = hipSuccess;
+  if (p.sq == 0 || p.sk == 0) {
+    // nothing contributes: "+=" leaves the gradients alone, "=" makes them zero
+    if (dq && !p.acc_dq && p.sq > 0) e = launch_zero_tensor(p.dq, p.batch, p.sq, p.q_heads, p.head_dim, stream);
+    if (e == hipSuccess && dk && !p.acc_dk && p.sk > 0)
+      e = launch_zero_tensor(p.dk, p.batch, p.sk, p.kv_heads, p.head_dim, stream);
+    if (e == hipSuccess && dv && !p.acc_dv && p.sk > 0)
+      e = launch_zero_tensor(p.dv, p.batch, p.sk, p.kv_heads, p.head_dim, stream);
+  } else {
+    e = launch_step_bwd(p, stream);
+  }
+  return e == hipSuccess ? BURST_OK : hip_fail(e);
+}
+
+static int fill_common(int32_t dev_i, int32_t shard_j, int32_t G, int64_t N, burst_mask_t* out) {
+  if (!out || G < 1 || dev_i < 0 || dev_i >= G || shard_j < 0 || shard_j >= G || N < 0) return BURST_ERR_INVALID_ARG;
+  std::memset(out, 0, sizeof(*out));
+  return BURST_OK;
+}
+
+int burst_attn_fill_zigzag_mask(int32_t dev_i, int32_t shard_j, int32_t G, int64_t N, int32_t causal,
+                                burst_mask_t* out) {
+  BURST_TRY(fill_common(dev_i, shard_j, G, N, out));
+  if (N % (2 * (int64_t)G)) return BURST_ERR_INVALID_ARG;
+  const int64_t P = N / (2 * (int64_t)G);
+  out->mode = causal ? BURST_MASK_CAUSAL : BURST_MASK_FULL;
+  out->q_nseg = out->k_nseg = 2;
+  out->q_seg_len = out->k_seg_len = P;
+  out->q_seg_pos[0] = dev_i * P;
+  out->q_seg_pos[1] = N - (dev_i + 1) * P;
+  out->k_seg_pos[0] = shard_j * P;
+  out->k_seg_pos[1] = N - (shard_j + 1) * P;
+  out->pos_stride = 1;
+  return BURST_OK;
+}
+
+int burst_attn_fill_contiguous_mask(int32_t dev_i, int32_t shard_j, int32_t G, int64_t N, int32_t causal,
+                                    burst_mask_t* out) {
+  BURST_TRY(fill_common(dev_i, shard_j, G, N, out));
+  if (N % G) return BURST_ERR_INVALID_ARG;
+  const int64_t n = N / G;
+  out->mode = causal ? BURST_MASK_CAUSAL : BURST_MASK_FULL;
+  out->q_nseg = out->k_nseg = 1;
+  out->q_seg_len = out->k_seg_len = n;
+  out->q_seg_pos[0] = dev_i * n;
+  out->k_seg_pos[0] = shard_j * n;
+  out->pos_stride = 1;
+  return BURST_OK;
+}
+
+int burst_attn_fill_striped_mask(int32_t dev_i, int32_t shard_j, int32_t G, int64_t N, int32_t causal,
+                                 burst_mask_t* out) {
+  BURST_TRY(fill_common(dev_i, shard_j, G, N, out));
+  if (N % G) return BURST_ERR_INVALID_ARG;
+  const int64_t n = N / G;
+  out->mode = causal ? BURST_MASK_CAUSAL : BURST_MASK_FULL;
+  out->q_nseg = out->k_nseg = 1;
+  out->q_seg_len = out->k_seg_len = n;
+  out->q_seg_pos[0] = dev_i;
+  out->k_seg_pos[0] = shard_j;
+  out->pos_stride = G;
+  return BURST_OK;
+}
+
+int64_t burst_attn_visible_pairs(const burst_mask_t* m) {
+  if (!m || m->q_nseg < 1 || m->q_nseg > 2 || m->k_nseg < 1 || m->k_nseg > 2 || m->q_seg_len < 0 ||
+      m->k_seg_len < 0 || m->pos_stride < 1)
+    return -1;
+  if (m->mode == BURST_MASK_FULL) return m->q_nseg * m->q_seg_len * m->k_nseg * m->k_seg_len;
+  if (m->mode != BURST_MASK_CAUSAL) return -1;
+  int64_t total = 0;
+  const int64_t s = m->pos_stride;
+  for (int qs = 0; qs < m->q_nseg; ++qs)
+    for (int ks = 0; ks < m->k_nseg; ++ks) {
+      const int64_t a = m->q_seg_pos[qs], b = m->k_seg_pos[ks];
+      for (int64_t i = 0; i < m->q_seg_len; ++i) {
+        // keys j with b + j*s <= a + i*s
+        const int64_t diff = a + i * s - b;
+        if (diff < 0) continue;
+        int64_t cnt = diff / s + 1;
+        if (cnt > m->k_seg_len) cnt = m->k_seg_len;
+        total += cnt;
+      }
+    }
+  return total;
+}
+
+const char* burst_attn_status_string(int status) {
+  switch (status) {
+    case BURST_OK: return "ok";
+    case BURST_ERR_INVALID_ARG: return "invalid argument";
+    case BURST_ERR_UNSUPPORTED: return "unsupported dtype, head_dim or position range";
+    case BURST_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int burst_attn_last_hip_error(void) { return g_last_hip_error; }
+
+const char* burst_attn_version(void) { return "libburstattn 0.1 (gfx950)"; }
+
+}  // extern "C"

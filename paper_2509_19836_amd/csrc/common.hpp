@@ -1,0 +1,188 @@
+// Shared device-side building blocks of libburstattn's gfx950 kernels.
+//
+// MFMA 32x32x16 bf16 register layouts (lane l: r = l % 32, h = l / 32):
+//   A operand (M x K): lane holds A[m = r][k = 8h .. 8h+7]
+//   B operand (K x N): lane holds B[k = 8h .. 8h+7][n = r]
+//   C/D (M x N), 16 fp32: register v holds C[m = 8*(v/4) + 4h + v%4][n = r]
+// The contraction index k may be permuted freely as long as A and B use the same permutation.
+// An accumulator tile whose M index is the next contraction index can therefore be fed back as
+// an operand after a bf16 pack: registers 8c .. 8c+7 of lane (r, h) hold the eight M rows
+//   16c + 8t + 4h + j   (t = 0,1; j = 0..3)
+// of column r, and the other operand only has to be read in that same row order.
+//
+// LDS tiles are row-major [rows][D] bf16 with a row pitch of 2*D + 16 bytes (a multiple of 16 B
+// that is an odd number of 16 B units, so 16 lanes reading 16 B from 16 different rows hit 64
+// different banks).  Rows are stored permuted inside each group of 16: tile row 16c + 4a + b sits
+// at LDS row 16c + 4b + a.  With that, the four rows a transposing read needs per 16-lane group
+// (tile rows 8t+4h+0..3) are four LDS rows 4 apart, i.e. 16 banks apart: conflict free.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace burst {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+enum TileClass : int { TILE_SKIP = 0, TILE_FULL = 1, TILE_PARTIAL = 2 };
+
+// Device copy of the visibility description; positions fit in int32 (checked on the host).
+struct MaskDev {
+  int32_t causal;
+  int32_t q_nseg, k_nseg;
+  int32_t q_seg_len, k_seg_len;
+  int32_t q_seg_pos[2], k_seg_pos[2];
+  int32_t pos_stride;
+};
+
+// A [batch, seq, heads, D] tensor; strides in elements.
+struct TensorDev {
+  void* ptr;
+  int64_t sb, ss, sh;
+  int32_t is_f32;
+};
+struct RowvecDev {
+  float* ptr;
+  int64_t sb, sh;
+};
+
+__device__ __forceinline__ int seg_position(int row, int nseg, int seg_len, const int32_t* seg_pos, int stride) {
+  int s = (nseg > 1 && row >= seg_len) ? 1 : 0;
+  return seg_pos[s] + (row - s * seg_len) * stride;
+}
+
+// min / max position over local rows [row0, row1), row1 > row0
+__device__ __forceinline__ void range_minmax(int row0, int row1, int nseg, int seg_len, const int32_t* seg_pos,
+                                             int stride, int& lo, int& hi) {
+  int last = row1 - 1;
+  if (nseg > 1 && row0 < seg_len && last >= seg_len) {
+    int lo0 = seg_pos[0] + row0 * stride, hi0 = seg_pos[0] + (seg_len - 1) * stride;
+    int lo1 = seg_pos[1], hi1 = seg_pos[1] + (last - seg_len) * stride;
+    lo = min(lo0, lo1);
+    hi = max(hi0, hi1);
+  } else {
+    lo = seg_position(row0, nseg, seg_len, seg_pos, stride);
+    hi = seg_position(last, nseg, seg_len, seg_pos, stride);
+  }
+}
+
+// Classify the block of query rows [q0, q1) against key rows [k0, k0 + kblock) of a chunk with sk rows.
+// PARTIAL = needs the per-element predicate (mask edge crosses it, or it holds rows >= sk).
+__device__ __forceinline__ int classify(const MaskDev& mk, int q0, int q1, int k0, int kblock, int sk) {
+  int k1 = min(k0 + kblock, sk);
+  if (k1 <= k0 || q1 <= q0) return TILE_SKIP;
+  bool ragged = (k0 + kblock > sk);
+  if (!mk.causal) return ragged ? TILE_PARTIAL : TILE_FULL;
+  int qlo, qhi, klo, khi;
+  range_minmax(q0, q1, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, qlo, qhi);
+  range_minmax(k0, k1, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride, klo, khi);
+  if (qhi < klo) return TILE_SKIP;
+  if (qlo >= khi && !ragged) return TILE_FULL;
+  return TILE_PARTIAL;
+}
+
+__device__ __forceinline__ int lds_row(int tile_row) {
+  // tile row 16c + 4a + b  ->  LDS row 16c + 4b + a
+  return (tile_row & ~15) | ((tile_row & 3) << 2) | ((tile_row >> 2) & 3);
+}
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Operand with lane = tile row, eight consecutive columns: rows row_base + r (r = lane % 32),
+// columns col0 + 8h .. +7 (bf16 elements).
+template <int PITCH>
+__device__ __forceinline__ bf16x8 lds_rows_operand(const char* tile, int row_base, int col0, int r, int h) {
+  const char* p = tile + lds_row(row_base + r) * PITCH + (col0 + 8 * h) * 2;
+  return *reinterpret_cast<const bf16x8*>(p);
+}
+
+// Operand with lane = tile column, eight rows: column col_base + r, rows
+// row16 + 8t + 4h + j (t = 0,1; j = 0..3) of a 16-row group starting at tile row row16
+// (a multiple of 16).  Element order 4t + j, matching packed accumulator registers.
+template <int PITCH>
+__device__ __forceinline__ bf16x8 lds_cols_operand(const char* tile, int row16, int col_base, int lane) {
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  const int i16 = lane & 15, g2 = (lane >> 4) & 1, h = lane >> 5;
+  // LDS row of tile row 8t+4h+j is 4j + 2t + h; lanes 4j .. 4j+3 of a 16-lane group supply row j
+  const int j = i16 >> 2;
+  const char* p = tile + (row16 + 4 * j + h) * PITCH + (col_base + 16 * g2 + 4 * (i16 & 3)) * 2;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 2 * PITCH));
+  typedef __attribute__((ext_vector_type(8))) short s16x8;
+  s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, both);
+}
+
+__device__ __forceinline__ float half_swap(float x) {
+  // value held by the lane 32 away
+  return __shfl_xor(x, 32, 64);
+}
+
+// Stage a [ROWS x D] bf16 tile: global (row-major, row stride `ss` elements, rows clamped to
+// [0, nrows-1]) -> registers -> LDS.  256 threads.  Split in two so the loads can be issued before
+// the compute they overlap with.
+template <int D, int ROWS>
+struct TileStager {
+  static constexpr int CPR = D / 8;              // 16-byte chunks per row
+  static constexpr int RPP = 256 / CPR;          // rows per pass
+  static constexpr int PASSES = ROWS / RPP;
+  static constexpr int PITCH = 2 * D + 16;
+  static_assert(ROWS % RPP == 0, "tile rows must be a multiple of rows per pass");
+  u32x4 regs[PASSES];
+
+  __device__ __forceinline__ void load(const __bf16* base, int64_t ss, int row0, int nrows, int tid) {
+    const int c = tid % CPR, rr = tid / CPR;
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i) {
+      int row = min(row0 + rr + i * RPP, nrows - 1);
+      regs[i] = *reinterpret_cast<const u32x4*>(base + (int64_t)row * ss + c * 8);
+    }
+  }
+  __device__ __forceinline__ void store(char* tile, int tid) const {
+    const int c = tid % CPR, rr = tid / CPR;
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i) {
+      *reinterpret_cast<u32x4*>(tile + lds_row(rr + i * RPP) * PITCH + c * 16) = regs[i];
+    }
+  }
+};
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16& x, int c) {
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (__bf16)x[8 * c + e];
+  return o;
+}
+
+// Work-group index -> (kv key = batch*Hkv + kv head, head within group, q tile), such that all work
+// on one (batch, kv head) lands on one XCD (work-groups are dealt round-robin to the 8 XCDs, each
+// with its own L2) and heavier tiles (higher rows) start first.
+struct BlockMap {
+  int key, head_in_group, tile;
+  bool valid;
+};
+__device__ __forceinline__ BlockMap map_block(int n, int n_keys, int group, int tiles) {
+  const int xcd = n & 7, slot = n >> 3;
+  const int per_key = group * tiles;
+  BlockMap m;
+  int local_key = slot / per_key, rem = slot - local_key * per_key;
+  m.key = local_key * 8 + xcd;
+  m.head_in_group = rem / tiles;
+  m.tile = tiles - 1 - (rem - m.head_in_group * tiles);
+  m.valid = m.key < n_keys;
+  return m;
+}
+inline int mapped_grid(int n_keys, int group, int tiles) { return 8 * ((n_keys + 7) / 8) * group * tiles; }
+
+}  // namespace burst

@@ -1,0 +1,55 @@
+// Kernel parameter blocks and host-side launchers shared between the C-ABI layer and the kernels.
+#pragma once
+#include "common.hpp"
+
+namespace burst {
+
+// Rows may keep a stale running maximum until one of the wave's rows grows by more than
+// 2^kLazyLog2; exp2 arguments then stay <= kLazyLog2, far inside fp32 / bf16 range.
+constexpr float kLazyLog2 = 6.0f;
+
+struct FwdParams {
+  int32_t batch, q_heads, kv_heads, head_dim;
+  int32_t sq, sk;
+  float scale;
+  MaskDev mask;
+  TensorDev q, k, v;
+  TensorDev o_part;     // ptr == nullptr: not requested
+  RowvecDev lse_part;
+  TensorDev o_acc;      // ptr == nullptr: no fused merge
+  RowvecDev lse_acc;
+};
+
+struct BwdParams {
+  int32_t batch, q_heads, kv_heads, head_dim;
+  int32_t sq, sk;
+  float scale;
+  MaskDev mask;
+  TensorDev q, k, v, d_o;
+  RowvecDev lse, d;
+  TensorDev dq, dk, dv;   // fp32; ptr == nullptr: skip
+  int32_t acc_dq, acc_dk, acc_dv;
+};
+
+struct MergeParams {
+  int32_t batch, q_heads, head_dim, sq;
+  TensorDev o_acc, o_part, o_out;   // o_out.ptr may be nullptr
+  RowvecDev lse_acc, lse_part;
+};
+
+struct PreParams {
+  int32_t batch, q_heads, head_dim, sq;
+  TensorDev o, d_o;
+  RowvecDev d;
+};
+
+hipError_t launch_step_fwd(const FwdParams& p, hipStream_t stream);
+hipError_t launch_step_bwd(const BwdParams& p, hipStream_t stream);
+hipError_t launch_lse_merge(const MergeParams& p, hipStream_t stream);
+hipError_t launch_preprocess_bwd(const PreParams& p, hipStream_t stream);
+// o_part = 0 / lse_part = -inf for a step with no key rows; zero-fill of fp32 gradients
+hipError_t launch_fill_empty_fwd(const FwdParams& p, hipStream_t stream);
+hipError_t launch_zero_tensor(const TensorDev& t, int32_t batch, int32_t rows, int32_t heads, int32_t head_dim,
+                              hipStream_t stream);
+
+}  // namespace burst
