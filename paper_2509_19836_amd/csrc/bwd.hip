@@ -1,5 +1,323 @@
+// Backward step kernels (Alg. 2 lines 7-13, with the softmax scale restored):
+//   S = scale Q K^T; P = exp(S - Lse); dV += P^T dO; dP = dO V^T; dS = P o (dP - D);
+//   dK += scale dS^T Q; dQ += scale dS K.
+//
+// Two kernels, each owning its outputs outright (no atomics, results are run-to-run identical):
+//
+//  * dQ kernel, query-stationary (same orientation as the forward kernel): a lane owns one query
+//    row; S^T = K Q^T and dP^T = V dO^T come out with the key index in the accumulator registers,
+//    dS^T is packed to bf16 in place and fed back as the B operand of dQ^T = K^T dS^T, whose A
+//    operand is the K tile read column-wise (transposing LDS reads) from the same LDS copy that
+//    served S^T row-wise.
+//
+//  * dK/dV kernel, key-stationary: a lane owns one key row; K and V rows live in registers as B
+//    operands, S = Q K^T and dP = dO V^T come out with the query index in the accumulator registers,
+//    P and dS are packed in place and fed back as B operands of dV^T = dO^T P and dK^T = Q^T dS,
+//    whose A operands are the dO and Q tiles read column-wise from the LDS copies that served
+//    S and dP row-wise.  With grouped-query attention the work-group walks the query heads of its
+//    group, so dK and dV are summed over the group in registers.
 #include "common.hpp"
 #include "kernels.hpp"
+
 namespace burst {
-hipError_t launch_step_bwd(const BwdParams& p, hipStream_t stream) { return hipErrorNotSupported; }
+
+// lse in log2 units, with -inf mapped to +inf so that exp2(x - lse2) = 0 for a dead row
+__device__ __forceinline__ float lse_to_log2(float lse) { return lse == -INFINITY ? INFINITY : lse * kLog2e; }
+
+__device__ __forceinline__ void zero16(f32x16& x) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v) x[v] = 0.f;
 }
+
+// ---------------------------------------------------------------------------------------------
+template <int D, int KB>
+__global__ __launch_bounds__(256, 2) void step_bwd_dq_kernel(BwdParams p) {
+  constexpr int BK = 32 * KB, DK = D / 16, DB = D / 32, BQ = 128;
+  constexpr int PITCH = 2 * D + 16;
+  constexpr int TILE = BK * PITCH;
+  extern __shared__ __attribute__((aligned(16))) char smem[];  // [2 buffers][K tile, V tile]
+
+  const int group = p.q_heads / p.kv_heads;
+  const int q_tiles = (p.sq + BQ - 1) / BQ;
+  const BlockMap bm = map_block(blockIdx.x, p.batch * p.kv_heads, group, q_tiles);
+  if (!bm.valid) return;
+  const int b = bm.key / p.kv_heads, hk = bm.key - b * p.kv_heads, hq = hk * group + bm.head_in_group;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
+  const int sq = p.sq, sk = p.sk;
+  const MaskDev mk = p.mask;
+  const int q_blk0 = bm.tile * BQ, q_blk1 = min(q_blk0 + BQ, sq);
+  const int q_w0 = q_blk0 + wave * 32, q_w1 = min(q_w0 + 32, sq);
+
+  const __bf16* kg = (const __bf16*)p.k.ptr + b * p.k.sb + hk * p.k.sh;
+  const __bf16* vg = (const __bf16*)p.v.ptr + b * p.v.sb + hk * p.v.sh;
+
+  const int row = min(q_w0 + r, sq - 1);
+  const int qpos = seg_position(row, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride);
+  bf16x8 qreg[DK], doreg[DK];
+  {
+    const __bf16* qs = (const __bf16*)p.q.ptr + b * p.q.sb + hq * p.q.sh + (int64_t)row * p.q.ss + 8 * h;
+    const __bf16* gs = (const __bf16*)p.d_o.ptr + b * p.d_o.sb + hq * p.d_o.sh + (int64_t)row * p.d_o.ss + 8 * h;
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) {
+      qreg[ks] = *reinterpret_cast<const bf16x8*>(qs + ks * 16);
+      doreg[ks] = *reinterpret_cast<const bf16x8*>(gs + ks * 16);
+    }
+  }
+  const float lse2 = lse_to_log2(p.lse.ptr[b * p.lse.sb + hq * p.lse.sh + row]);
+  const float dval = p.d.ptr[b * p.d.sb + hq * p.d.sh + row];
+  const float c = p.scale * kLog2e;
+
+  f32x16 dq[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) zero16(dq[db]);
+
+  const int n_tiles = (sk + BK - 1) / BK;
+  auto next_tile = [&](int t) {
+    while (t < n_tiles && classify(mk, q_blk0, q_blk1, t * BK, min(t * BK + BK, sk), false) == TILE_SKIP) ++t;
+    return t;
+  };
+
+  TileStager<D, BK> stage_k, stage_v;
+  int t = next_tile(0);
+  if (t < n_tiles) {
+    stage_k.load(kg, p.k.ss, t * BK, sk, tid);
+    stage_v.load(vg, p.v.ss, t * BK, sk, tid);
+    stage_k.store(smem, tid);
+    stage_v.store(smem + TILE, tid);
+  }
+  __syncthreads();
+  int buf = 0;
+  while (t < n_tiles) {
+    const int tn = next_tile(t + 1);
+    if (tn < n_tiles) {
+      stage_k.load(kg, p.k.ss, tn * BK, sk, tid);
+      stage_v.load(vg, p.v.ss, tn * BK, sk, tid);
+    }
+    const char* kt = smem + buf * 2 * TILE;
+    const char* vt = kt + TILE;
+    const int cls = classify(mk, q_w0, q_w1, t * BK, min(t * BK + BK, sk), t * BK + BK > sk);
+    if (cls != TILE_SKIP) {
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) {
+        f32x16 s, dp;
+        zero16(s);
+        zero16(dp);
+#pragma unroll
+        for (int ks = 0; ks < DK; ++ks) {
+          s = mfma32(lds_rows_operand<PITCH>(kt, kb * 32, ks * 16, r, h), qreg[ks], s);
+          dp = mfma32(lds_rows_operand<PITCH>(vt, kb * 32, ks * 16, r, h), doreg[ks], dp);
+        }
+        if (cls == TILE_PARTIAL) mask_tile<true>(s, mk, t * BK + kb * 32 + 4 * h, sk, qpos);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float pr = __builtin_amdgcn_exp2f(c * s[v] - lse2);
+          s[v] = pr * (dp[v] - dval);
+        }
+        bf16x8 ds0 = pack8(s, 0), ds1 = pack8(s, 1);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          dq[db] = mfma32(lds_cols_operand<PITCH>(kt, kb * 32, db * 32, lane), ds0, dq[db]);
+          dq[db] = mfma32(lds_cols_operand<PITCH>(kt, kb * 32 + 16, db * 32, lane), ds1, dq[db]);
+        }
+      }
+    }
+    if (tn < n_tiles) {
+      char* nk = smem + (buf ^ 1) * 2 * TILE;
+      stage_k.store(nk, tid);
+      stage_v.store(nk + TILE, tid);
+    }
+    __syncthreads();
+    t = tn;
+    buf ^= 1;
+  }
+
+  if (q_w0 + r < sq) {
+    float* dst = (float*)p.dq.ptr + b * p.dq.sb + (int64_t)(q_w0 + r) * p.dq.ss + hq * p.dq.sh;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float* q4 = dst + db * 32 + 8 * g + 4 * h;
+        f32x4 x = {dq[db][4 * g] * p.scale, dq[db][4 * g + 1] * p.scale, dq[db][4 * g + 2] * p.scale,
+                   dq[db][4 * g + 3] * p.scale};
+        if (p.acc_dq) x += *reinterpret_cast<const f32x4*>(q4);
+        *reinterpret_cast<f32x4*>(q4) = x;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+template <int D, int BQ>
+__global__ __launch_bounds__(256, 1) void step_bwd_dkdv_kernel(BwdParams p) {
+  constexpr int DK = D / 16, DB = D / 32, QBK = BQ / 32, BKV = 128;
+  constexpr int PITCH = 2 * D + 16;
+  constexpr int TILE = BQ * PITCH;
+  constexpr int BUF = 2 * TILE + 2 * BQ * 4;   // Q tile, dO tile, lse2[BQ], D[BQ]
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  const int group = p.q_heads / p.kv_heads;
+  const int kv_tiles = (p.sk + BKV - 1) / BKV;
+  const BlockMap bm = map_block(blockIdx.x, p.batch * p.kv_heads, 1, kv_tiles);
+  if (!bm.valid) return;
+  const int b = bm.key / p.kv_heads, hk = bm.key - b * p.kv_heads;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
+  const int sq = p.sq, sk = p.sk;
+  const MaskDev mk = p.mask;
+  const int k_blk0 = bm.tile * BKV, k_blk1 = min(k_blk0 + BKV, sk);
+  const int k_w0 = k_blk0 + wave * 32, k_w1 = min(k_w0 + 32, sk);
+
+  const int krow = min(k_w0 + r, sk - 1);
+  const int kpos = seg_position(krow, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride);
+  bf16x8 kreg[DK], vreg[DK];
+  {
+    const __bf16* ks_ = (const __bf16*)p.k.ptr + b * p.k.sb + hk * p.k.sh + (int64_t)krow * p.k.ss + 8 * h;
+    const __bf16* vs_ = (const __bf16*)p.v.ptr + b * p.v.sb + hk * p.v.sh + (int64_t)krow * p.v.ss + 8 * h;
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks) {
+      kreg[ks] = *reinterpret_cast<const bf16x8*>(ks_ + ks * 16);
+      vreg[ks] = *reinterpret_cast<const bf16x8*>(vs_ + ks * 16);
+    }
+  }
+  const float c = p.scale * kLog2e;
+
+  f32x16 dk[DB], dv[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) {
+    zero16(dk[db]);
+    zero16(dv[db]);
+  }
+
+  // flattened walk over (query head of the group, query tile), skipping tiles the mask empties
+  const int q_tiles = (sq + BQ - 1) / BQ;
+  const int n_items = group * q_tiles;
+  auto next_item = [&](int it) {
+    while (it < n_items) {
+      int qt = it % q_tiles;
+      if (classify(mk, qt * BQ, min(qt * BQ + BQ, sq), k_blk0, k_blk1, false) != TILE_SKIP) break;
+      ++it;
+    }
+    return it;
+  };
+
+  TileStager<D, BQ> stage_q, stage_do;
+  float stage_row = 0.f;   // threads [0, BQ): lse2 of a row; threads [BQ, 2*BQ): D of a row
+  auto issue = [&](int it) {
+    const int hq = hk * group + it / q_tiles, q0 = (it % q_tiles) * BQ;
+    stage_q.load((const __bf16*)p.q.ptr + b * p.q.sb + hq * p.q.sh, p.q.ss, q0, sq, tid);
+    stage_do.load((const __bf16*)p.d_o.ptr + b * p.d_o.sb + hq * p.d_o.sh, p.d_o.ss, q0, sq, tid);
+    if (tid < 2 * BQ) {
+      const int rr = min(q0 + (tid % BQ), sq - 1);
+      stage_row = (tid < BQ) ? lse_to_log2(p.lse.ptr[b * p.lse.sb + hq * p.lse.sh + rr])
+                             : p.d.ptr[b * p.d.sb + hq * p.d.sh + rr];
+    }
+  };
+  auto commit = [&](char* dst) {
+    stage_q.store(dst, tid);
+    stage_do.store(dst + TILE, tid);
+    if (tid < 2 * BQ) reinterpret_cast<float*>(dst + 2 * TILE)[tid] = stage_row;
+  };
+
+  int it = next_item(0);
+  if (it < n_items) {
+    issue(it);
+    commit(smem);
+  }
+  __syncthreads();
+  int buf = 0;
+  while (it < n_items) {
+    const int itn = next_item(it + 1);
+    if (itn < n_items) issue(itn);
+    const char* qt_ = smem + buf * BUF;
+    const char* dot_ = qt_ + TILE;
+    const float* rowv = reinterpret_cast<const float*>(qt_ + 2 * TILE);
+    const int q0 = (it % q_tiles) * BQ;
+#pragma unroll
+    for (int qb = 0; qb < QBK; ++qb) {
+      const int qb0 = q0 + qb * 32;
+      const int cls = classify(mk, qb0, min(qb0 + 32, sq), k_w0, k_w1, qb0 + 32 > sq);   // wave-uniform
+      if (cls == TILE_SKIP) continue;
+      f32x16 s, dp;
+      zero16(s);
+      zero16(dp);
+#pragma unroll
+      for (int ks = 0; ks < DK; ++ks) {
+        s = mfma32(lds_rows_operand<PITCH>(qt_, qb * 32, ks * 16, r, h), kreg[ks], s);
+        dp = mfma32(lds_rows_operand<PITCH>(dot_, qb * 32, ks * 16, r, h), vreg[ks], dp);
+      }
+      if (cls == TILE_PARTIAL) mask_tile<false>(s, mk, qb0 + 4 * h, sq, kpos);
+      f32x16 ds;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(rowv + qb * 32 + 8 * g + 4 * h);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(rowv + BQ + qb * 32 + 8 * g + 4 * h);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float pr = __builtin_amdgcn_exp2f(c * s[4 * g + j] - l4[j]);
+          s[4 * g + j] = pr;
+          ds[4 * g + j] = pr * (dp[4 * g + j] - d4[j]);
+        }
+      }
+      bf16x8 p0 = pack8(s, 0), p1 = pack8(s, 1), ds0 = pack8(ds, 0), ds1 = pack8(ds, 1);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        dv[db] = mfma32(lds_cols_operand<PITCH>(dot_, qb * 32, db * 32, lane), p0, dv[db]);
+        dv[db] = mfma32(lds_cols_operand<PITCH>(dot_, qb * 32 + 16, db * 32, lane), p1, dv[db]);
+        dk[db] = mfma32(lds_cols_operand<PITCH>(qt_, qb * 32, db * 32, lane), ds0, dk[db]);
+        dk[db] = mfma32(lds_cols_operand<PITCH>(qt_, qb * 32 + 16, db * 32, lane), ds1, dk[db]);
+      }
+    }
+    if (itn < n_items) commit(smem + (buf ^ 1) * BUF);
+    __syncthreads();
+    it = itn;
+    buf ^= 1;
+  }
+
+  if (k_w0 + r < sk) {
+    float* dkp = (float*)p.dk.ptr + b * p.dk.sb + (int64_t)(k_w0 + r) * p.dk.ss + hk * p.dk.sh;
+    float* dvp = (float*)p.dv.ptr + b * p.dv.sb + (int64_t)(k_w0 + r) * p.dv.ss + hk * p.dv.sh;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int off = db * 32 + 8 * g + 4 * h;
+        f32x4 xk = {dk[db][4 * g] * p.scale, dk[db][4 * g + 1] * p.scale, dk[db][4 * g + 2] * p.scale,
+                    dk[db][4 * g + 3] * p.scale};
+        f32x4 xv = {dv[db][4 * g], dv[db][4 * g + 1], dv[db][4 * g + 2], dv[db][4 * g + 3]};
+        if (p.acc_dk) xk += *reinterpret_cast<const f32x4*>(dkp + off);
+        if (p.acc_dv) xv += *reinterpret_cast<const f32x4*>(dvp + off);
+        *reinterpret_cast<f32x4*>(dkp + off) = xk;
+        *reinterpret_cast<f32x4*>(dvp + off) = xv;
+      }
+  }
+}
+
+template <int D>
+static hipError_t launch_bwd_t(const BwdParams& p, hipStream_t stream) {
+  const int n_keys = p.batch * p.kv_heads, group = p.q_heads / p.kv_heads;
+  if (p.dq.ptr) {
+    constexpr int KB = 2;
+    constexpr int LDS = 2 * 2 * 32 * KB * (2 * D + 16);
+    const int grid = mapped_grid(n_keys, group, (p.sq + 127) / 128);
+    hipLaunchKernelGGL((step_bwd_dq_kernel<D, KB>), dim3(grid), dim3(256), LDS, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  if (p.dk.ptr) {
+    constexpr int BQ = 64;
+    constexpr int LDS = 2 * (2 * BQ * (2 * D + 16) + 2 * BQ * 4);
+    const int grid = mapped_grid(n_keys, 1, (p.sk + 127) / 128);
+    hipLaunchKernelGGL((step_bwd_dkdv_kernel<D, BQ>), dim3(grid), dim3(256), LDS, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_step_bwd(const BwdParams& p, hipStream_t stream) {
+  if (p.head_dim == 128) return launch_bwd_t<128>(p, stream);
+  return launch_bwd_t<64>(p, stream);
+}
+
+}  // namespace burst

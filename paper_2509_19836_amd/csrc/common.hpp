@@ -75,12 +75,11 @@ __device__ __forceinline__ void range_minmax(int row0, int row1, int nseg, int s
   }
 }
 
-// Classify the block of query rows [q0, q1) against key rows [k0, k0 + kblock) of a chunk with sk rows.
-// PARTIAL = needs the per-element predicate (mask edge crosses it, or it holds rows >= sk).
-__device__ __forceinline__ int classify(const MaskDev& mk, int q0, int q1, int k0, int kblock, int sk) {
-  int k1 = min(k0 + kblock, sk);
+// Classify the block of query rows [q0, q1) against key rows [k0, k1) (both already clipped to the
+// chunk).  PARTIAL = needs the per-element predicate: the mask edge crosses the block, or the caller
+// says so because the register tile also covers rows beyond the end of a chunk.
+__device__ __forceinline__ int classify(const MaskDev& mk, int q0, int q1, int k0, int k1, bool ragged) {
   if (k1 <= k0 || q1 <= q0) return TILE_SKIP;
-  bool ragged = (k0 + kblock > sk);
   if (!mk.causal) return ragged ? TILE_PARTIAL : TILE_FULL;
   int qlo, qhi, klo, khi;
   range_minmax(q0, q1, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, qlo, qhi);
@@ -88,6 +87,29 @@ __device__ __forceinline__ int classify(const MaskDev& mk, int q0, int q1, int k
   if (qhi < klo) return TILE_SKIP;
   if (qlo >= khi && !ragged) return TILE_FULL;
   return TILE_PARTIAL;
+}
+
+// Per-element mask of one 32x32 accumulator tile whose 16 registers of a lane run over rows
+// row0 + 8*(v/4) + (v%4)  (row0 already includes the lane's 4*h) of the OTHER side than the lane's
+// own row: KEYS_IN_REGS = true, registers are key rows and the lane owns a query (position
+// lane_pos); false, registers are query rows and the lane owns a key.  Invisible entries and rows
+// >= n_rows become -inf.  Written with selects only, no divergent control flow.
+template <bool KEYS_IN_REGS>
+__device__ __forceinline__ void mask_tile(f32x16& s, const MaskDev& mk, int row0, int n_rows, int lane_pos) {
+  const int nseg = KEYS_IN_REGS ? mk.k_nseg : mk.q_nseg;
+  const int seg_len = KEYS_IN_REGS ? mk.k_seg_len : mk.q_seg_len;
+  const int pos0 = KEYS_IN_REGS ? mk.k_seg_pos[0] : mk.q_seg_pos[0];
+  const int pos1 = KEYS_IN_REGS ? mk.k_seg_pos[1] : mk.q_seg_pos[1];
+  const int split = nseg > 1 ? seg_len : 0x7fffffff;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int row = row0 + 8 * (v >> 2) + (v & 3);
+    const bool second = row >= split;
+    const int pos = (second ? pos1 : pos0) + (row - (second ? seg_len : 0)) * mk.pos_stride;
+    const bool ordered = KEYS_IN_REGS ? (lane_pos >= pos) : (pos >= lane_pos);
+    const bool vis = (row < n_rows) & ((mk.causal == 0) | ordered);
+    s[v] = vis ? s[v] : -INFINITY;
+  }
 }
 
 __device__ __forceinline__ int lds_row(int tile_row) {

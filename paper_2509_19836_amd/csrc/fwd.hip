@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256, 2) void step_fwd_kernel(FwdParams p) {
 
   const int n_tiles = (sk + BK - 1) / BK;
   auto next_tile = [&](int t) {
-    while (t < n_tiles && classify(mk, q_blk0, q_blk1, t * BK, BK, sk) == TILE_SKIP) ++t;
+    while (t < n_tiles && classify(mk, q_blk0, q_blk1, t * BK, min(t * BK + BK, sk), false) == TILE_SKIP) ++t;
     return t;
   };
 
@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256, 2) void step_fwd_kernel(FwdParams p) {
     }
     const char* kt = smem + buf * 2 * TILE;
     const char* vt = kt + TILE;
-    const int cls = classify(mk, q_w0, q_w1, t * BK, BK, sk);   // wave-uniform
+    const int cls = classify(mk, q_w0, q_w1, t * BK, min(t * BK + BK, sk), t * BK + BK > sk);   // wave-uniform
     if (cls != TILE_SKIP) {
       f32x16 s[KB][QB];
 #pragma unroll
@@ -108,15 +108,7 @@ __global__ __launch_bounds__(256, 2) void step_fwd_kernel(FwdParams p) {
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            int krow = t * BK + kb * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-            int kpos = seg_position(krow, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride);
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-              bool vis = (krow < sk) && (!mk.causal || qpos[qb] >= kpos);
-              if (!vis) s[kb][qb][v] = -INFINITY;
-            }
-          }
+          for (int qb = 0; qb < QB; ++qb) mask_tile<true>(s[kb][qb], mk, t * BK + kb * 32 + 4 * h, sk, qpos[qb]);
       }
       bf16x8 pp[QB][KB][2];
 #pragma unroll
