@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of libburstattn on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch: device i's complete simulated ring
+-- G forward steps with the fused online-softmax merge, the D = rowsum(dO o O) preprocess, and G
+backward steps (dQ_i accumulated locally, dK_j / dV_j produced for every visiting shard) -- at the
+real per-device shard shape with every KV shard resident in HBM.  The reported value is
+unmasked-FLOP throughput: visible (q, k) pairs x (4 d forward + 10 d backward) / time.
+
+Prints ONE JSON line.  Per-kernel durations are taken inside the timed region with HIP events on
+the stream the kernels are launched on (torch's current stream).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
+
+
+def cpu_baseline(w, kind, dev_i, shard_j, sample_rows, seed):
+    """The fp64 oracle, untuned, on a bounded sample of the same workload: `sample_rows` query rows
+    (evenly spaced over the chunk) of one (batch, head) against one whole KV shard, forward step +
+    backward step.  Returns TFLOPS with the same unmasked-FLOP count."""
+    import numpy as np
+    from oracle import burst_oracle as oc
+    from paper_2509_19836_amd import workloads as wl
+    G, N, d = w.shards, w.seq, w.head_dim
+    pos_fn = {"zigzag": oc.zigzag_positions, "full": oc.contiguous_positions, "causal": oc.contiguous_positions}[kind]
+    qpos_all, kpos = pos_fn(dev_i, G, N), pos_fn(shard_j, G, N)
+    sel = np.linspace(0, qpos_all.size - 1, sample_rows).astype(np.int64)
+    rng = np.random.Generator(np.random.PCG64(seed))
+    draw = lambda n: wl.bf16_bits_to_f64(wl.f32_to_bf16_bits(rng.standard_normal((n, d), dtype=np.float32)))
+    Q, dO, K, V = draw(sample_rows), draw(sample_rows), draw(kpos.size), draw(kpos.size)
+    vis = oc.visibility(qpos_all[sel], kpos, kind != "full")
+    pairs = int(vis.sum())
+    t0 = time.perf_counter()
+    O, lse = oc.step_fwd(Q, K, V, w.scale, vis)
+    D = oc.preprocess_bwd(dO, O)
+    oc.step_bwd(Q, K, V, dO, lse, D, w.scale, vis)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": pairs * 14 * d / dt / 1e12, "unit": "TFLOPS", "cores": int(cores), "kind": "oracle",
+            "seconds": round(dt, 3),
+            "sample": f"{sample_rows} evenly spaced query rows of one (batch, head) against one full "
+                      f"{kpos.size}-row KV shard (device {dev_i} vs shard {shard_j}, {kind}), forward step "
+                      f"+ D + backward step in fp64 numpy; {pairs} visible pairs"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=2, help="workload index (1-5) of the benchmark definition")
+    ap.add_argument("--device-index", type=int, default=3, help="which simulated device's ring to run")
+    ap.add_argument("--cpu-sample-rows", type=int, default=16384)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build measures the per-device compute step on ONE GPU; the ring is simulated "
+                 "in HBM and there is no multi-GPU path (--gpus must be 1)")
+
+    import torch
+    from paper_2509_19836_amd import binding as lib, ring, workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS[args.config]
+    kind, G, N, i = w.mask, w.shards, w.seq, args.device_index % w.shards
+    n, d, B, Hq, Hkv = w.shard_tokens, w.head_dim, w.batch, w.q_heads, w.kv_heads
+
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(wl.BASE_SEED + 100 * args.config)
+
+    def draw(heads):
+        x = torch.randn(B, n, heads, d, device="cuda", dtype=torch.float32, generator=gen)
+        if w.head_scale:
+            x = x * torch.empty(B, 1, heads, 1, device="cuda").uniform_(0.5, 2.0, generator=gen)
+        return x.to(torch.bfloat16)
+
+    q_i, do_i = draw(Hq), draw(Hq)
+    ks, vs = [draw(Hkv) for _ in range(G)], [draw(Hkv) for _ in range(G)]
+    f32 = dict(device="cuda", dtype=torch.float32)
+    o_acc = torch.empty(B, n, Hq, d, **f32)
+    lse_acc = torch.empty(B, Hq, n, **f32)
+    d_i = torch.empty(B, Hq, n, **f32)
+    dq = torch.empty(B, n, Hq, d, **f32)
+    dks = [torch.empty(B, n, Hkv, d, **f32) for _ in range(G)]
+    dvs = [torch.empty(B, n, Hkv, d, **f32) for _ in range(G)]
+
+    order = ring.ring_order(i, G)
+    masks = {j: ring.fill_mask(kind, i, j, G, N) for j in order}
+    pairs = {j: lib.burst_attn_visible_pairs(masks[j]) for j in order}
+    shp = lib.shape(B, Hq, Hkv, d, n, n, w.scale)
+    DQ, DKV = lib.BURST_ACC_DQ, lib.BURST_ACC_DK | lib.BURST_ACC_DV
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    spans = {"step_fwd": [], "step_bwd_dq": [], "step_bwd_dkdv": [], "preprocess_bwd": []}
+
+    def reset():   # outside the timed region
+        o_acc.zero_()
+        lse_acc.fill_(-float("inf"))
+        dq.zero_()
+        for t in dks + dvs:
+            t.zero_()
+
+    def one_ring(record):
+        marks = []
+        def span(name, fn):
+            if record:
+                a, b = ev(), ev()
+                a.record(); fn(); b.record()
+                marks.append((name, a, b))
+            else:
+                fn()
+        for j in order:
+            span("step_fwd", lambda: lib.burst_attn_step_fwd(shp, masks[j], q_i, ks[j], vs[j], o_acc=o_acc, lse_acc=lse_acc))
+        span("preprocess_bwd", lambda: lib.burst_attn_preprocess_bwd(shp, o_acc, do_i, d_i))
+        for j in order:
+            # the two launches burst_attn_step_bwd makes for (dq, dk, dv), bracketed one by one
+            span("step_bwd_dq", lambda: lib.burst_attn_step_bwd(shp, masks[j], q_i, ks[j], vs[j], do_i, lse_acc, d_i,
+                                                               dq=dq, accumulate_flags=DQ))
+            span("step_bwd_dkdv", lambda: lib.burst_attn_step_bwd(shp, masks[j], q_i, ks[j], vs[j], do_i, lse_acc, d_i,
+                                                                 dk=dks[j], dv=dvs[j], accumulate_flags=DKV))
+        return marks
+
+    for _ in range(args.warmup):
+        reset()
+        one_ring(False)
+    torch.cuda.synchronize()
+    total_s, all_marks = 0.0, []
+    for _ in range(args.steps):
+        reset()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        marks = one_ring(True)
+        torch.cuda.synchronize()
+        total_s += time.perf_counter() - t0
+        all_marks += marks
+    for name, a, b in all_marks:
+        spans[name].append(a.elapsed_time(b))
+    assert torch.isfinite(o_acc).all() and torch.isfinite(dq).all(), "non-finite result"
+
+    ring_pairs = sum(pairs.values()) * B * Hq
+    fl_fwd, fl_bwd = ring_pairs * 4 * d, ring_pairs * 10 * d
+    ms_ring = total_s / args.steps * 1e3
+    avg = {k: sum(v) / len(v) for k, v in spans.items() if v}
+    fwd_ms, bwd_ms = avg["step_fwd"] * G, (avg["step_bwd_dq"] + avg["step_bwd_dkdv"]) * G
+    value = (fl_fwd + fl_bwd) / (ms_ring * 1e-3) / 1e12
+
+    # roofline of the dominant kernel (key-stationary dK/dV kernel).  Of the 10 d flop per visible
+    # pair of a backward step it is charged 6 d: dV (2 d), dK (2 d) and half of the S and dP GEMMs
+    # (2 d) that both backward kernels recompute; the dQ kernel carries the other 4 d.
+    per_launch_pairs = sum(pairs.values()) / G * B * Hq
+    dom_flops = per_launch_pairs * 6 * d
+    achieved = dom_flops / (avg["step_bwd_dkdv"] * 1e-3) / 1e12
+    out = {
+        "metric": "attention fwd+bwd TFLOPS per ring step (unmasked FLOPs)",
+        "value": round(value, 2), "unit": "TFLOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_ring, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name} (config {args.config}): device {i} of {G}, one full simulated ring = "
+                               f"{G} fwd steps + D + {G} bwd steps, B={B} Hq={Hq} Hkv={Hkv} d={d}, "
+                               f"Q chunk {n} x {G} KV chunks of {n}, mask {kind}",
+                   "ring_steps_per_step": G, "ms_per_ring_step": round(ms_ring / G, 3)},
+        "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
+        "fwd_tflops": round(fl_fwd / (fwd_ms * 1e-3) / 1e12, 2),
+        "bwd_tflops": round(fl_bwd / (bwd_ms * 1e-3) / 1e12, 2),
+        "kernel_ms": {k: round(v, 4) for k, v in avg.items()},
+        "roofline": {"bound": "mfma", "kernel": "step_bwd_dkdv_kernel", "achieved": round(achieved, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None,
+                     "issued_tflops": round(per_launch_pairs * 8 * d / (avg["step_bwd_dkdv"] * 1e-3) / 1e12, 2)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, kind, i, order[1 % G], args.cpu_sample_rows, wl.BASE_SEED + 5)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,52 @@
+"""Simulated ring driver: the host loop of one device's pass over all KV shards.
+
+On one GPU the ring is simulated: every KV shard already sits in HBM and device i visits them in
+ring order, its own shard first and then j = (i - t) mod G (Sec. 3.4; forward algorithm lines
+3-12; Alg. 1 for the backward order used here: Q_i, dO_i, Lse_i, D_i stay and dQ_i accumulates
+locally while dK_j, dV_j of the visiting shard accumulate).  Nothing here computes: each step is
+one call into the C ABI.
+"""
+from . import binding as lib
+
+
+def ring_order(i, G):
+    return [(i - t) % G for t in range(G)]
+
+
+def fill_mask(kind, i, j, G, N):
+    """kind: "full" / "causal" (contiguous split), "zigzag", "striped"."""
+    if kind == "full":
+        return lib.burst_attn_fill_contiguous_mask(i, j, G, N, False)
+    if kind == "causal":
+        return lib.burst_attn_fill_contiguous_mask(i, j, G, N, True)
+    if kind == "zigzag":
+        return lib.burst_attn_fill_zigzag_mask(i, j, G, N, True)
+    if kind == "striped":
+        return lib.burst_attn_fill_striped_mask(i, j, G, N, True)
+    raise ValueError(kind)
+
+
+def ring_forward(i, G, N, kind, scale, q_i, k_shards, v_shards, o_acc, lse_acc, stream=None):
+    """o_acc / lse_acc must hold (0, -inf) on entry; they hold (O_i, Lse_i) on return."""
+    B, n, Hq, d = q_i.shape
+    for j in ring_order(i, G):
+        k_j, v_j = k_shards[j], v_shards[j]
+        shp = lib.shape(B, Hq, k_j.shape[2], d, n, k_j.shape[1], scale)
+        lib.burst_attn_step_fwd(shp, fill_mask(kind, i, j, G, N), q_i, k_j, v_j,
+                                o_acc=o_acc, lse_acc=lse_acc, stream=stream)
+
+
+def ring_backward(i, G, N, kind, scale, q_i, do_i, o_i, lse_i, d_i, k_shards, v_shards, dq_i, dk_shards,
+                  dv_shards, stream=None):
+    """D_i once, then one backward step per shard; dq_i, dk_shards[j], dv_shards[j] are fp32
+    accumulators ("+=")."""
+    B, n, Hq, d = q_i.shape
+    shp0 = lib.shape(B, Hq, k_shards[0].shape[2], d, n, n, scale)
+    lib.burst_attn_preprocess_bwd(shp0, o_i, do_i, d_i, stream=stream)
+    flags = lib.BURST_ACC_DQ | lib.BURST_ACC_DK | lib.BURST_ACC_DV
+    for j in ring_order(i, G):
+        k_j, v_j = k_shards[j], v_shards[j]
+        shp = lib.shape(B, Hq, k_j.shape[2], d, n, k_j.shape[1], scale)
+        lib.burst_attn_step_bwd(shp, fill_mask(kind, i, j, G, N), q_i, k_j, v_j, do_i, lse_i, d_i,
+                                dq=dq_i, dk=dk_shards[j], dv=dv_shards[j], accumulate_flags=flags,
+                                stream=stream)

@@ -1,0 +1,174 @@
+"""CPU-only checks of the C-ABI boundary: the library loads and exports what the header declares,
+the host helpers agree with the oracle's partitions, and invalid arguments are rejected before
+anything could reach a GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import burst_oracle as oc
+from tests import helpers as hp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "burst_attn.h")).read()
+    declared = set(re.findall(r"\b(burst_attn_\w+)\s*\(", header))
+    assert {"burst_attn_step_fwd", "burst_attn_lse_merge", "burst_attn_step_bwd",
+            "burst_attn_preprocess_bwd"} <= declared
+    raw = lib.raw()
+    for name in sorted(declared):
+        assert hasattr(raw, name), f"{name} declared in the header but not exported"
+    assert declared == set(lib.EXPORTS)
+    assert "gfx950" in lib.burst_attn_version()
+
+
+def test_struct_layouts_match_the_header(lib):
+    # natural C layout of the structs in include/burst_attn.h
+    assert C.sizeof(lib.burst_shape_t) == 40
+    assert C.sizeof(lib.burst_tensor_t) == 40
+    assert C.sizeof(lib.burst_rowvec_t) == 24
+    assert C.sizeof(lib.burst_mask_t) == 16 + 32 + 24
+
+
+@pytest.mark.parametrize("G,N", [(1, 8), (2, 24), (4, 64), (8, 128)])
+def test_mask_helpers_agree_with_oracle_partitions(lib, G, N):
+    for kind in ("causal", "zigzag", "striped"):
+        for i in range(G):
+            for j in range(G):
+                m = hp.fill_mask(lib, kind, i, j, G, N)
+                qpos, kpos = hp.mask_positions(m, "q"), hp.mask_positions(m, "k")
+                assert (qpos == hp.oracle_positions(oc, kind, i, G, N)).all()
+                assert (kpos == hp.oracle_positions(oc, kind, j, G, N)).all()
+                assert lib.burst_attn_visible_pairs(m) == oc.visible_pairs(qpos, kpos, True)
+    m = hp.fill_mask(lib, "full", 0, G - 1, G, N)
+    assert lib.burst_attn_visible_pairs(m) == (N // G) ** 2
+
+
+def test_zigzag_pair_counts_closed_form(lib):
+    # every step carries the same work: 2 P^2 pairs, plus P on the device's own shard (Sec. 3.4)
+    G, N = 8, 8 * 2 * 96
+    P = N // (2 * G)
+    for i in range(G):
+        for j in range(G):
+            got = lib.burst_attn_visible_pairs(lib.burst_attn_fill_zigzag_mask(i, j, G, N))
+            assert got == 2 * P * P + (P if i == j else 0)
+
+
+def test_mask_helper_argument_errors(lib):
+    raw = lib.raw()
+    m = lib.burst_mask_t()
+    assert raw.burst_attn_fill_zigzag_mask(0, 0, 4, 100, 1, C.byref(m)) == lib.BURST_ERR_INVALID_ARG  # 100 % 8
+    assert raw.burst_attn_fill_zigzag_mask(4, 0, 4, 64, 1, C.byref(m)) == lib.BURST_ERR_INVALID_ARG
+    assert raw.burst_attn_fill_contiguous_mask(0, -1, 4, 64, 1, C.byref(m)) == lib.BURST_ERR_INVALID_ARG
+    assert raw.burst_attn_fill_striped_mask(0, 0, 0, 64, 1, C.byref(m)) == lib.BURST_ERR_INVALID_ARG
+    assert raw.burst_attn_fill_zigzag_mask(0, 0, 4, 64, 1, None) == lib.BURST_ERR_INVALID_ARG
+    bad = lib.burst_mask_t(7, 1, 1, 0, (0, 0), (0, 0), 4, 4, 1)
+    assert lib.burst_attn_visible_pairs(bad) == -1
+    assert lib.burst_attn_status_string(lib.BURST_ERR_UNSUPPORTED).startswith("unsupported")
+
+
+def _fake_tensor(lib, dtype=0, ptr=0x10000, strides=(1 << 20, 256, 128)):
+    return lib.burst_tensor_t(ptr, dtype, 0, *strides)
+
+
+def _fake_rowvec(lib, ptr=0x20000):
+    return lib.burst_rowvec_t(ptr, 4096, 1024)
+
+
+def test_invalid_arguments_are_rejected_on_the_host(lib):
+    """None of these calls may get as far as a HIP call: they all fail validation first.  The
+    pointers are made-up numbers that are never dereferenced."""
+    raw = lib.raw()
+    ok_shape = lib.shape(1, 2, 2, 128, 64, 64, 0.1)
+    t, tf32, rv = _fake_tensor(lib), _fake_tensor(lib, dtype=1), _fake_rowvec(lib)
+    r = C.byref
+
+    def fwd(shape=ok_shape, mask=None, q=t, k=t, v=t, o_part=tf32, lse_part=rv, o_acc=None, lse_acc=None):
+        ref = lambda x: None if x is None else r(x)
+        return raw.burst_attn_step_fwd(ref(shape), ref(mask), ref(q), ref(k), ref(v), ref(o_part), ref(lse_part),
+                                       ref(o_acc), ref(lse_acc), None)
+
+    INV, UNS = lib.BURST_ERR_INVALID_ARG, lib.BURST_ERR_UNSUPPORTED
+    assert fwd(shape=None) == INV
+    assert fwd(q=None) == INV
+    assert fwd(o_part=None, lse_part=None) == INV                        # no output requested
+    assert fwd(lse_part=None) == INV                                     # o_part without lse_part
+    assert fwd(q=_fake_tensor(lib, ptr=0)) == INV                        # null data pointer
+    assert fwd(q=_fake_tensor(lib, ptr=0x10008)) == INV                  # misaligned
+    assert fwd(k=_fake_tensor(lib, strides=(1 << 20, 252, 128))) == INV  # stride not a multiple of 8
+    assert fwd(q=tf32) == UNS                                            # fp32 q not supported
+    assert fwd(o_acc=t, lse_acc=rv) == UNS                               # running state must be fp32
+    assert fwd(shape=lib.shape(1, 2, 2, 96, 64, 64, 0.1)) == UNS         # head_dim
+    assert fwd(shape=lib.shape(1, 3, 2, 128, 64, 64, 0.1)) == INV        # heads not divisible
+    assert fwd(shape=lib.shape(1, 2, 2, 128, 64, 64, 0.0)) == INV        # scale
+    assert fwd(shape=lib.shape(1, 2, 2, 128, 64, 64, float("nan"))) == INV
+    assert fwd(shape=lib.shape(0, 2, 2, 128, 64, 64, 0.1)) == INV
+    assert fwd(shape=lib.shape(1, 2, 2, 128, -1, 64, 0.1)) == INV
+    assert fwd(mask=lib.burst_mask_t(1, 1, 1, 0, (0, 0), (0, 0), 63, 64, 1)) == INV      # seg_len * nseg != sq
+    assert fwd(mask=lib.burst_mask_t(1, 3, 1, 0, (0, 0), (0, 0), 64, 64, 1)) == INV      # nseg
+    assert fwd(mask=lib.burst_mask_t(2, 1, 1, 0, (0, 0), (0, 0), 64, 64, 1)) == INV      # mode
+    assert fwd(mask=lib.burst_mask_t(1, 1, 1, 0, (0, 0), (0, 0), 64, 64, 0)) == INV      # stride
+    assert fwd(mask=lib.burst_mask_t(1, 1, 1, 0, (-5, 0), (0, 0), 64, 64, 1)) == INV     # negative position
+    assert fwd(mask=lib.burst_mask_t(1, 1, 1, 0, (1 << 31, 0), (0, 0), 64, 64, 1)) == UNS  # position range
+
+    def bwd(dq=tf32, dk=tf32, dv=tf32, flags=0, lse=rv, d=rv, d_o=t):
+        ref = lambda x: None if x is None else r(x)
+        return raw.burst_attn_step_bwd(r(ok_shape), None, r(t), r(t), r(t), ref(d_o), ref(lse), ref(d), ref(dq), ref(dk),
+                                       ref(dv), flags, None)
+
+    assert bwd(dq=None, dk=None, dv=None) == INV
+    assert bwd(dv=None) == INV                       # dk without dv
+    assert bwd(flags=8) == INV
+    assert bwd(lse=None) == INV
+    assert bwd(dq=t) == UNS                          # gradients are fp32
+    assert bwd(d_o=tf32) == UNS
+    assert raw.burst_attn_lse_merge(r(ok_shape), r(tf32), r(rv), r(tf32), None, None, None) == INV
+    assert raw.burst_attn_lse_merge(r(ok_shape), r(t), r(rv), r(tf32), r(rv), None, None) == UNS
+    assert raw.burst_attn_preprocess_bwd(r(ok_shape), r(tf32), r(tf32), r(rv), None) == UNS
+    assert raw.burst_attn_preprocess_bwd(r(ok_shape), r(tf32), r(t), None, None) == INV
+
+
+def test_empty_query_chunk_returns_ok_without_a_launch(lib):
+    raw = lib.raw()
+    t, tf32, rv = _fake_tensor(lib), _fake_tensor(lib, dtype=1), _fake_rowvec(lib)
+    shp = lib.shape(1, 2, 2, 128, 0, 64, 0.1)
+    assert raw.burst_attn_step_fwd(C.byref(shp), None, C.byref(t), C.byref(t), C.byref(t), C.byref(tf32), C.byref(rv),
+                                   None, None, None) == lib.BURST_OK
+    assert raw.burst_attn_lse_merge(C.byref(shp), C.byref(tf32), C.byref(rv), C.byref(tf32), C.byref(rv), None,
+                                    None) == lib.BURST_OK
+    assert raw.burst_attn_preprocess_bwd(C.byref(shp), C.byref(tf32), C.byref(t), C.byref(rv), None) == lib.BURST_OK
+
+
+def test_binding_refuses_to_load_without_the_library(tmp_path, monkeypatch):
+    """There is no CPU fallback: importing the binding without a built library raises."""
+    import importlib.util
+    src = os.path.join(ROOT, "paper_2509_19836_amd", "binding.py")
+    dst = tmp_path / "binding_copy.py"
+    dst.write_text(open(src).read())
+    spec = importlib.util.spec_from_file_location("binding_copy", dst)
+    mod = importlib.util.module_from_spec(spec)
+    with pytest.raises(ImportError, match="no CPU or PyTorch fallback"):
+        spec.loader.exec_module(mod)
+
+
+def test_workload_generators_are_seeded_and_exact():
+    from paper_2509_19836_amd import workloads as wl
+    w = wl.WORKLOADS[1]
+    a, b = wl.host_tensors(w, 1), wl.host_tensors(w, 1)
+    for n in a:
+        assert (a[n][1] == b[n][1]).all()
+    x = np.array([1.0, 1.00390625, -2.5, 3.1415927, 1e-30], dtype=np.float32)
+    bits = wl.f32_to_bf16_bits(x)
+    back = wl.bf16_bits_to_f32(bits)
+    assert back[0] == 1.0 and back[2] == -2.5
+    assert back[1] == 1.0            # 1 + 2^-8 is a tie: rounds to even
+    assert abs(back[3] - 3.140625) < 1e-6
+    assert (wl.bf16_bits_to_f64(bits) == back.astype(np.float64)).all()
+    w4 = wl.Workload("t", 2, 4, 4, 128, 64, 2, "full", True)
+    t4 = wl.host_tensors(w4, 4)
+    stds = t4["q"][0].std(axis=(1, 3))
+    assert stds.min() > 0.4 and stds.max() < 2.2 and stds.std() > 0.05
