@@ -78,6 +78,7 @@ __global__ __launch_bounds__(256, 2) void step_bwd_dq_kernel(BwdParams p) {
     return t;
   };
 
+  wait_global_loads();
   TileStager<D, BK> stage_k, stage_v;
   int t = next_tile(0);
   if (t < n_tiles) {
@@ -148,46 +149,42 @@ __global__ __launch_bounds__(256, 2) void step_bwd_dq_kernel(BwdParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-template <int D, int BQ>
-__global__ __launch_bounds__(256, 1) void step_bwd_dkdv_kernel(BwdParams p) {
-  constexpr int DK = D / 16, DB = D / 32, QBK = BQ / 32, BKV = 128;
+// Eight waves per work-group, two per SIMD, in two roles that share each block of 32 key rows:
+//   P-wave  (waves 0-3): K rows in registers; S = Q K^T, P = exp2(..) -> bf16, hands P over through
+//                        LDS, then dV^T += dO^T P.
+//   dS-wave (waves 4-7): V rows in registers; dP = dO V^T, then dS = P o (dP - D), dK^T += Q^T dS.
+// Each role carries one 32 x D accumulator and one stationary operand, which is what lets two
+// waves fit on a SIMD; the exp-heavy role and the light one overlap on the same SIMD.
+// Two barriers per query tile: [S, P | dP]  barrier  [dV | dS, dK; stage next tile]  barrier.
+template <int D, int BQ, int ROLE>
+__device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b, int hk, int kv_tile, int pair) {
+  constexpr int DK = D / 16, DB = D / 32, QBK = BQ / 32, BKV = 128, NT = 512;
   constexpr int PITCH = 2 * D + 16;
   constexpr int TILE = BQ * PITCH;
   constexpr int BUF = 2 * TILE + 2 * BQ * 4;   // Q tile, dO tile, lse2[BQ], D[BQ]
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+  bf16x8* pbuf = reinterpret_cast<bf16x8*>(smem + 2 * BUF);     // [pair][qb][half][lane]
 
   const int group = p.q_heads / p.kv_heads;
-  const int kv_tiles = (p.sk + BKV - 1) / BKV;
-  const BlockMap bm = map_block(blockIdx.x, p.batch * p.kv_heads, 1, kv_tiles);
-  if (!bm.valid) return;
-  const int b = bm.key / p.kv_heads, hk = bm.key - b * p.kv_heads;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, h = lane >> 5;
   const int sq = p.sq, sk = p.sk;
   const MaskDev mk = p.mask;
-  const int k_blk0 = bm.tile * BKV, k_blk1 = min(k_blk0 + BKV, sk);
-  const int k_w0 = k_blk0 + wave * 32, k_w1 = min(k_w0 + 32, sk);
+  const int k_blk0 = kv_tile * BKV, k_blk1 = min(k_blk0 + BKV, sk);
+  const int k_w0 = k_blk0 + pair * 32, k_w1 = min(k_w0 + 32, sk);
 
   const int krow = min(k_w0 + r, sk - 1);
   const int kpos = seg_position(krow, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride);
-  bf16x8 kreg[DK], vreg[DK];
+  bf16x8 xreg[DK];   // K rows (P-wave) or V rows (dS-wave) as the B operand
   {
-    const __bf16* ks_ = (const __bf16*)p.k.ptr + b * p.k.sb + hk * p.k.sh + (int64_t)krow * p.k.ss + 8 * h;
-    const __bf16* vs_ = (const __bf16*)p.v.ptr + b * p.v.sb + hk * p.v.sh + (int64_t)krow * p.v.ss + 8 * h;
+    const TensorDev& src = ROLE == 0 ? p.k : p.v;
+    const __bf16* s_ = (const __bf16*)src.ptr + b * src.sb + hk * src.sh + (int64_t)krow * src.ss + 8 * h;
 #pragma unroll
-    for (int ks = 0; ks < DK; ++ks) {
-      kreg[ks] = *reinterpret_cast<const bf16x8*>(ks_ + ks * 16);
-      vreg[ks] = *reinterpret_cast<const bf16x8*>(vs_ + ks * 16);
-    }
+    for (int ks = 0; ks < DK; ++ks) xreg[ks] = *reinterpret_cast<const bf16x8*>(s_ + ks * 16);
   }
   const float c = p.scale * kLog2e;
 
-  f32x16 dk[DB], dv[DB];
+  f32x16 acc[DB];   // dV^T (P-wave) or dK^T (dS-wave)
 #pragma unroll
-  for (int db = 0; db < DB; ++db) {
-    zero16(dk[db]);
-    zero16(dv[db]);
-  }
+  for (int db = 0; db < DB; ++db) zero16(acc[db]);
 
   // flattened walk over (query head of the group, query tile), skipping tiles the mask empties
   const int q_tiles = (sq + BQ - 1) / BQ;
@@ -201,7 +198,7 @@ __global__ __launch_bounds__(256, 1) void step_bwd_dkdv_kernel(BwdParams p) {
     return it;
   };
 
-  TileStager<D, BQ> stage_q, stage_do;
+  TileStager<D, BQ, NT> stage_q, stage_do;
   float stage_row = 0.f;   // threads [0, BQ): lse2 of a row; threads [BQ, 2*BQ): D of a row
   auto issue = [&](int it) {
     const int hq = hk * group + it / q_tiles, q0 = (it % q_tiles) * BQ;
@@ -219,6 +216,7 @@ __global__ __launch_bounds__(256, 1) void step_bwd_dkdv_kernel(BwdParams p) {
     if (tid < 2 * BQ) reinterpret_cast<float*>(dst + 2 * TILE)[tid] = stage_row;
   };
 
+  wait_global_loads();
   int it = next_item(0);
   if (it < n_items) {
     issue(it);
@@ -233,39 +231,61 @@ __global__ __launch_bounds__(256, 1) void step_bwd_dkdv_kernel(BwdParams p) {
     const char* dot_ = qt_ + TILE;
     const float* rowv = reinterpret_cast<const float*>(qt_ + 2 * TILE);
     const int q0 = (it % q_tiles) * BQ;
+    // Class of the whole query tile against this pair's 32 key rows (same for both waves of the
+    // pair).  A tile the mask only partly empties is computed whole with the per-element predicate.
+    const int cls = classify(mk, q0, min(q0 + BQ, sq), k_w0, k_w1, q0 + BQ > sq);
+    if (ROLE == 0) {
+      bf16x8 pk[2 * QBK];
+      if (cls != TILE_SKIP) {
+        f32x16 s[QBK];
 #pragma unroll
-    for (int qb = 0; qb < QBK; ++qb) {
-      const int qb0 = q0 + qb * 32;
-      const int cls = classify(mk, qb0, min(qb0 + 32, sq), k_w0, k_w1, qb0 + 32 > sq);   // wave-uniform
-      if (cls == TILE_SKIP) continue;
-      f32x16 s, dp;
-      zero16(s);
-      zero16(dp);
+        for (int qb = 0; qb < QBK; ++qb) zero16(s[qb]);
+        gemm_rows<PITCH, QBK, DK, 2>(qt_, 0, xreg, s, r, h);
 #pragma unroll
-      for (int ks = 0; ks < DK; ++ks) {
-        s = mfma32(lds_rows_operand<PITCH>(qt_, qb * 32, ks * 16, r, h), kreg[ks], s);
-        dp = mfma32(lds_rows_operand<PITCH>(dot_, qb * 32, ks * 16, r, h), vreg[ks], dp);
-      }
-      if (cls == TILE_PARTIAL) mask_tile<false>(s, mk, qb0 + 4 * h, sq, kpos);
-      f32x16 ds;
+        for (int qb = 0; qb < QBK; ++qb) {
+          if (cls == TILE_PARTIAL) mask_tile<false>(s[qb], mk, q0 + qb * 32 + 4 * h, sq, kpos);
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const f32x4 l4 = *reinterpret_cast<const f32x4*>(rowv + qb * 32 + 8 * g + 4 * h);
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(rowv + BQ + qb * 32 + 8 * g + 4 * h);
+          for (int g = 0; g < 4; ++g) {
+            const f32x4 l4 = *reinterpret_cast<const f32x4*>(rowv + qb * 32 + 8 * g + 4 * h);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          float pr = __builtin_amdgcn_exp2f(c * s[4 * g + j] - l4[j]);
-          s[4 * g + j] = pr;
-          ds[4 * g + j] = pr * (dp[4 * g + j] - d4[j]);
+            for (int j = 0; j < 4; ++j) s[qb][4 * g + j] = __builtin_amdgcn_exp2f(c * s[qb][4 * g + j] - l4[j]);
+          }
+          pk[2 * qb] = pack8(s[qb], 0);
+          pk[2 * qb + 1] = pack8(s[qb], 1);
+          pbuf[((pair * QBK + qb) * 2 + 0) * 64 + lane] = pk[2 * qb];
+          pbuf[((pair * QBK + qb) * 2 + 1) * 64 + lane] = pk[2 * qb + 1];
         }
       }
-      bf16x8 p0 = pack8(s, 0), p1 = pack8(s, 1), ds0 = pack8(ds, 0), ds1 = pack8(ds, 1);
+      __syncthreads();
+      if (cls != TILE_SKIP) gemm_cols<PITCH, DB, 2 * QBK, 1>(dot_, 0, pk, acc, lane);
+    } else {
+      f32x16 dp[QBK];
+      if (cls != TILE_SKIP) {
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        dv[db] = mfma32(lds_cols_operand<PITCH>(dot_, qb * 32, db * 32, lane), p0, dv[db]);
-        dv[db] = mfma32(lds_cols_operand<PITCH>(dot_, qb * 32 + 16, db * 32, lane), p1, dv[db]);
-        dk[db] = mfma32(lds_cols_operand<PITCH>(qt_, qb * 32, db * 32, lane), ds0, dk[db]);
-        dk[db] = mfma32(lds_cols_operand<PITCH>(qt_, qb * 32 + 16, db * 32, lane), ds1, dk[db]);
+        for (int qb = 0; qb < QBK; ++qb) zero16(dp[qb]);
+        gemm_rows<PITCH, QBK, DK, 2>(dot_, 0, xreg, dp, r, h);
+      }
+      __syncthreads();
+      if (cls != TILE_SKIP) {
+        bf16x8 dsp[2 * QBK];
+#pragma unroll
+        for (int qb = 0; qb < QBK; ++qb) {
+          const bf16x8 q0_ = pbuf[((pair * QBK + qb) * 2 + 0) * 64 + lane];
+          const bf16x8 q1_ = pbuf[((pair * QBK + qb) * 2 + 1) * 64 + lane];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const f32x4 d4 = *reinterpret_cast<const f32x4*>(rowv + BQ + qb * 32 + 8 * g + 4 * h);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const int v = 4 * g + j;
+              const float pr = (float)(v < 8 ? q0_[v & 7] : q1_[v & 7]);
+              dp[qb][v] = pr * (dp[qb][v] - d4[j]);
+            }
+          }
+          dsp[2 * qb] = pack8(dp[qb], 0);
+          dsp[2 * qb + 1] = pack8(dp[qb], 1);
+        }
+        gemm_cols<PITCH, DB, 2 * QBK, 1>(qt_, 0, dsp, acc, lane);
       }
     }
     if (itn < n_items) commit(smem + (buf ^ 1) * BUF);
@@ -275,22 +295,34 @@ __global__ __launch_bounds__(256, 1) void step_bwd_dkdv_kernel(BwdParams p) {
   }
 
   if (k_w0 + r < sk) {
-    float* dkp = (float*)p.dk.ptr + b * p.dk.sb + (int64_t)(k_w0 + r) * p.dk.ss + hk * p.dk.sh;
-    float* dvp = (float*)p.dv.ptr + b * p.dv.sb + (int64_t)(k_w0 + r) * p.dv.ss + hk * p.dv.sh;
+    const TensorDev& dst = ROLE == 0 ? p.dv : p.dk;
+    const bool accumulate = ROLE == 0 ? p.acc_dv : p.acc_dk;
+    const float mul = ROLE == 0 ? 1.f : p.scale;
+    float* dp_ = (float*)dst.ptr + b * dst.sb + (int64_t)(k_w0 + r) * dst.ss + hk * dst.sh;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int off = db * 32 + 8 * g + 4 * h;
-        f32x4 xk = {dk[db][4 * g] * p.scale, dk[db][4 * g + 1] * p.scale, dk[db][4 * g + 2] * p.scale,
-                    dk[db][4 * g + 3] * p.scale};
-        f32x4 xv = {dv[db][4 * g], dv[db][4 * g + 1], dv[db][4 * g + 2], dv[db][4 * g + 3]};
-        if (p.acc_dk) xk += *reinterpret_cast<const f32x4*>(dkp + off);
-        if (p.acc_dv) xv += *reinterpret_cast<const f32x4*>(dvp + off);
-        *reinterpret_cast<f32x4*>(dkp + off) = xk;
-        *reinterpret_cast<f32x4*>(dvp + off) = xv;
+        f32x4 x = {acc[db][4 * g] * mul, acc[db][4 * g + 1] * mul, acc[db][4 * g + 2] * mul, acc[db][4 * g + 3] * mul};
+        if (accumulate) x += *reinterpret_cast<const f32x4*>(dp_ + off);
+        *reinterpret_cast<f32x4*>(dp_ + off) = x;
       }
   }
+}
+
+template <int D, int BQ>
+__global__ __launch_bounds__(512, 1) void step_bwd_dkdv_kernel(BwdParams p) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // [2][tile buffers], then the P hand-over area
+  const int kv_tiles = (p.sk + 127) / 128;
+  const BlockMap bm = map_block(blockIdx.x, p.batch * p.kv_heads, 1, kv_tiles);
+  if (!bm.valid) return;
+  const int b = bm.key / p.kv_heads, hk = bm.key - b * p.kv_heads;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: the role branch is uniform
+  // Two complete, separate instruction streams (same barrier count per tile in both), so that each
+  // role is register-allocated on its own.
+  if (wave < 4) dkdv_role<D, BQ, 0>(p, smem, b, hk, bm.tile, wave);
+  else dkdv_role<D, BQ, 1>(p, smem, b, hk, bm.tile, wave - 4);
 }
 
 template <int D>
@@ -306,9 +338,9 @@ static hipError_t launch_bwd_t(const BwdParams& p, hipStream_t stream) {
   }
   if (p.dk.ptr) {
     constexpr int BQ = 64;
-    constexpr int LDS = 2 * (2 * BQ * (2 * D + 16) + 2 * BQ * 4);
+    constexpr int LDS = 2 * (2 * BQ * (2 * D + 16) + 2 * BQ * 4) + 4 * (BQ / 32) * 2 * 64 * 16;
     const int grid = mapped_grid(n_keys, 1, (p.sk + 127) / 128);
-    hipLaunchKernelGGL((step_bwd_dkdv_kernel<D, BQ>), dim3(grid), dim3(256), LDS, stream, p);
+    hipLaunchKernelGGL((step_bwd_dkdv_kernel<D, BQ>), dim3(grid), dim3(512), LDS, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

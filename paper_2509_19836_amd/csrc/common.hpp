@@ -146,18 +146,24 @@ __device__ __forceinline__ bf16x8 lds_cols_operand(const char* tile, int row16, 
   return __builtin_bit_cast(bf16x8, both);
 }
 
+// Wait for every outstanding global load of this wave.  Used once, before a tile loop, after the
+// loop-invariant register operands were fetched: without it the compiler cannot prove on every
+// path that they have landed and re-inserts vmcnt waits inside the loop, which then also wait for
+// the tile prefetch issued just before them.
+__device__ __forceinline__ void wait_global_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+
 __device__ __forceinline__ float half_swap(float x) {
   // value held by the lane 32 away
   return __shfl_xor(x, 32, 64);
 }
 
 // Stage a [ROWS x D] bf16 tile: global (row-major, row stride `ss` elements, rows clamped to
-// [0, nrows-1]) -> registers -> LDS.  256 threads.  Split in two so the loads can be issued before
+// [0, nrows-1]) -> registers -> LDS, by THREADS threads.  Split in two so the loads can be issued before
 // the compute they overlap with.
-template <int D, int ROWS>
+template <int D, int ROWS, int THREADS = 256>
 struct TileStager {
   static constexpr int CPR = D / 8;              // 16-byte chunks per row
-  static constexpr int RPP = 256 / CPR;          // rows per pass
+  static constexpr int RPP = THREADS / CPR;      // rows per pass
   static constexpr int PASSES = ROWS / RPP;
   static constexpr int PITCH = 2 * D + 16;
   static_assert(ROWS % RPP == 0, "tile rows must be a multiple of rows per pass");
@@ -179,6 +185,54 @@ struct TileStager {
     }
   }
 };
+
+// acc[nb] += A_nb * B for NB row blocks of an LDS tile: A_nb = tile rows row0 + 32*nb .. +31 (all D
+// columns, read row-wise), B = DK register operands.  The k-step is the outer loop so consecutive
+// MFMAs hit different accumulators, and LDS operands are fetched PRE k-steps ahead of their use;
+// the scheduling fences keep the compiler from hoisting more (registers) or less (latency).
+template <int PITCH, int NB, int DK, int PRE>
+__device__ __forceinline__ void gemm_rows(const char* tile, int row0, const bf16x8 (&breg)[DK], f32x16 (&acc)[NB],
+                                          int r, int h) {
+  bf16x8 a[DK][NB];
+#pragma unroll
+  for (int ks = 0; ks < PRE && ks < DK; ++ks)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) a[ks][nb] = lds_rows_operand<PITCH>(tile, row0 + 32 * nb, ks * 16, r, h);
+#pragma unroll
+  for (int ks = 0; ks < DK; ++ks) {
+    if (ks + PRE < DK) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+        a[ks + PRE][nb] = lds_rows_operand<PITCH>(tile, row0 + 32 * nb, (ks + PRE) * 16, r, h);
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma32(a[ks][nb], breg[ks], acc[nb]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// acc[db] += A_db,c * b[c]: A = LDS tile read column-wise (columns 32*db .. +31, rows
+// row0 + 16*c .. +15 in packed-accumulator order), b[c] = packed register operands, c < NC.
+// One step = one 16-row chunk across all DB accumulators; operands fetched PRE steps ahead.
+template <int PITCH, int DB, int NC, int PRE>
+__device__ __forceinline__ void gemm_cols(const char* tile, int row0, const bf16x8 (&b)[NC], f32x16 (&acc)[DB],
+                                          int lane) {
+  bf16x8 a[NC][DB];
+#pragma unroll
+  for (int c = 0; c < PRE && c < NC; ++c)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) a[c][db] = lds_cols_operand<PITCH>(tile, row0 + 16 * c, db * 32, lane);
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    if (c + PRE < NC) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db) a[c + PRE][db] = lds_cols_operand<PITCH>(tile, row0 + 16 * (c + PRE), db * 32, lane);
+    }
+#pragma unroll
+    for (int db = 0; db < DB; ++db) acc[db] = mfma32(a[c][db], b[c], acc[db]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
 
 __device__ __forceinline__ bf16x8 pack8(const f32x16& x, int c) {
   bf16x8 o;

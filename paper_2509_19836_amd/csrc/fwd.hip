@@ -70,6 +70,7 @@ __global__ __launch_bounds__(256, 2) void step_fwd_kernel(FwdParams p) {
     return t;
   };
 
+  wait_global_loads();
   TileStager<D, BK> stage_k, stage_v;
   int t = next_tile(0);
   if (t < n_tiles) {
@@ -92,13 +93,17 @@ __global__ __launch_bounds__(256, 2) void step_fwd_kernel(FwdParams p) {
     if (cls != TILE_SKIP) {
       f32x16 s[KB][QB];
 #pragma unroll
-      for (int kb = 0; kb < KB; ++kb) {
+      for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
           for (int v = 0; v < 16; ++v) s[kb][qb][v] = 0.f;
+      // k-step outermost: consecutive MFMAs go to different accumulators (a dependent
+      // accumulate chain issues at little more than half rate)
 #pragma unroll
-        for (int ks = 0; ks < DK; ++ks) {
+      for (int ks = 0; ks < DK; ++ks) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
           bf16x8 a = lds_rows_operand<PITCH>(kt, kb * 32, ks * 16, r, h);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) s[kb][qb] = mfma32(a, qreg[qb][ks], s[kb][qb]);
