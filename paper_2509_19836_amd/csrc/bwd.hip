@@ -38,15 +38,14 @@ __global__ __launch_bounds__(256, 2) void step_bwd_dq_kernel(BwdParams p) {
   extern __shared__ __attribute__((aligned(16))) char smem[];  // [2 buffers][K tile, V tile]
 
   const int group = p.q_heads / p.kv_heads;
-  const int q_tiles = (p.sq + BQ - 1) / BQ;
-  const BlockMap bm = map_block(blockIdx.x, p.batch * p.kv_heads, group, q_tiles);
+  const BlockMap bm = map_block(blockIdx.x, p.batch * p.kv_heads, group, p.q_runs.total());
   if (!bm.valid) return;
   const int b = bm.key / p.kv_heads, hk = bm.key - b * p.kv_heads, hq = hk * group + bm.head_in_group;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
   const int sq = p.sq, sk = p.sk;
   const MaskDev mk = p.mask;
-  const int q_blk0 = bm.tile * BQ, q_blk1 = min(q_blk0 + BQ, sq);
+  const int q_blk0 = p.q_runs.tile_of(bm.tile) * BQ, q_blk1 = min(q_blk0 + BQ, sq);
   const int q_w0 = q_blk0 + wave * 32, q_w1 = min(q_w0 + 32, sq);
 
   const __bf16* kg = (const __bf16*)p.k.ptr + b * p.k.sb + hk * p.k.sh;
@@ -78,14 +77,16 @@ __global__ __launch_bounds__(256, 2) void step_bwd_dq_kernel(BwdParams p) {
     return t;
   };
 
-  wait_global_loads();
   TileStager<D, BK> stage_k, stage_v;
+  stage_k.init(p.k.ss, tid);
+  stage_v.init(p.v.ss, tid);
+  wait_global_loads();
   int t = next_tile(0);
   if (t < n_tiles) {
     stage_k.load(kg, p.k.ss, t * BK, sk, tid);
     stage_v.load(vg, p.v.ss, t * BK, sk, tid);
-    stage_k.store(smem, tid);
-    stage_v.store(smem + TILE, tid);
+    stage_k.store(smem);
+    stage_v.store(smem + TILE);
   }
   __syncthreads();
   int buf = 0;
@@ -101,32 +102,24 @@ __global__ __launch_bounds__(256, 2) void step_bwd_dq_kernel(BwdParams p) {
     if (cls != TILE_SKIP) {
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb) {
-        f32x16 s, dp;
-        zero16(s);
-        zero16(dp);
-#pragma unroll
-        for (int ks = 0; ks < DK; ++ks) {
-          s = mfma32(lds_rows_operand<PITCH>(kt, kb * 32, ks * 16, r, h), qreg[ks], s);
-          dp = mfma32(lds_rows_operand<PITCH>(vt, kb * 32, ks * 16, r, h), doreg[ks], dp);
-        }
-        if (cls == TILE_PARTIAL) mask_tile<true>(s, mk, t * BK + kb * 32 + 4 * h, sk, qpos);
+        f32x16 sd[2];   // S^T and dP^T of this key block: two independent accumulator chains
+        zero16(sd[0]);
+        zero16(sd[1]);
+        gemm_rows_pair<PITCH, DK, 2>(kt, vt, kb * 32, qreg, doreg, sd[0], sd[1], r, h);
+        if (cls == TILE_PARTIAL) mask_tile<true>(sd[0], mk, t * BK + kb * 32 + 4 * h, sk, qpos);
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          float pr = __builtin_amdgcn_exp2f(c * s[v] - lse2);
-          s[v] = pr * (dp[v] - dval);
+          float pr = __builtin_amdgcn_exp2f(c * sd[0][v] - lse2);
+          sd[0][v] = pr * (sd[1][v] - dval);
         }
-        bf16x8 ds0 = pack8(s, 0), ds1 = pack8(s, 1);
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          dq[db] = mfma32(lds_cols_operand<PITCH>(kt, kb * 32, db * 32, lane), ds0, dq[db]);
-          dq[db] = mfma32(lds_cols_operand<PITCH>(kt, kb * 32 + 16, db * 32, lane), ds1, dq[db]);
-        }
+        bf16x8 ds[2] = {pack8(sd[0], 0), pack8(sd[0], 1)};
+        gemm_cols<PITCH, DB, 2, 1>(kt, kb * 32, ds, dq, lane);
       }
     }
     if (tn < n_tiles) {
       char* nk = smem + (buf ^ 1) * 2 * TILE;
-      stage_k.store(nk, tid);
-      stage_v.store(nk + TILE, tid);
+      stage_k.store(nk);
+      stage_v.store(nk + TILE);
     }
     __syncthreads();
     t = tn;
@@ -168,7 +161,7 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, h = lane >> 5;
   const int sq = p.sq, sk = p.sk;
   const MaskDev mk = p.mask;
-  const int k_blk0 = kv_tile * BKV, k_blk1 = min(k_blk0 + BKV, sk);
+  const int k_blk0 = p.k_runs.tile_of(kv_tile) * BKV, k_blk1 = min(k_blk0 + BKV, sk);
   const int k_w0 = k_blk0 + pair * 32, k_w1 = min(k_w0 + 32, sk);
 
   const int krow = min(k_w0 + r, sk - 1);
@@ -199,6 +192,8 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
   };
 
   TileStager<D, BQ, NT> stage_q, stage_do;
+  stage_q.init(p.q.ss, tid);
+  stage_do.init(p.d_o.ss, tid);
   float stage_row = 0.f;   // threads [0, BQ): lse2 of a row; threads [BQ, 2*BQ): D of a row
   auto issue = [&](int it) {
     const int hq = hk * group + it / q_tiles, q0 = (it % q_tiles) * BQ;
@@ -211,8 +206,8 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
     }
   };
   auto commit = [&](char* dst) {
-    stage_q.store(dst, tid);
-    stage_do.store(dst + TILE, tid);
+    stage_q.store(dst);
+    stage_do.store(dst + TILE);
     if (tid < 2 * BQ) reinterpret_cast<float*>(dst + 2 * TILE)[tid] = stage_row;
   };
 
@@ -314,8 +309,7 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
 template <int D, int BQ>
 __global__ __launch_bounds__(512, 1) void step_bwd_dkdv_kernel(BwdParams p) {
   extern __shared__ __attribute__((aligned(16))) char smem[];   // [2][tile buffers], then the P hand-over area
-  const int kv_tiles = (p.sk + 127) / 128;
-  const BlockMap bm = map_block(blockIdx.x, p.batch * p.kv_heads, 1, kv_tiles);
+  const BlockMap bm = map_block(blockIdx.x, p.batch * p.kv_heads, 1, p.k_runs.total());
   if (!bm.valid) return;
   const int b = bm.key / p.kv_heads, hk = bm.key - b * p.kv_heads;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: the role branch is uniform
@@ -326,23 +320,40 @@ __global__ __launch_bounds__(512, 1) void step_bwd_dkdv_kernel(BwdParams p) {
 }
 
 template <int D>
-static hipError_t launch_bwd_t(const BwdParams& p, hipStream_t stream) {
+static hipError_t launch_bwd_t(BwdParams p, hipStream_t stream) {
   const int n_keys = p.batch * p.kv_heads, group = p.q_heads / p.kv_heads;
+  hipError_t e = hipSuccess;
   if (p.dq.ptr) {
     constexpr int KB = 2;
     constexpr int LDS = 2 * 2 * 32 * KB * (2 * D + 16);
-    const int grid = mapped_grid(n_keys, group, (p.sq + 127) / 128);
-    hipLaunchKernelGGL((step_bwd_dq_kernel<D, KB>), dim3(grid), dim3(256), LDS, stream, p);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    p.q_runs = nonempty_runs(p.mask, p.sq, p.sk, 128, true);
+    // query tiles that see no key get no work-group: "=" must still leave zeros there
+    if (!p.acc_dq && p.q_runs.total() < (p.sq + 127) / 128) {
+      e = launch_zero_tensor(p.dq, p.batch, p.sq, p.q_heads, p.head_dim, stream);
+      if (e != hipSuccess) return e;
+    }
+    if (p.q_runs.total() > 0) {
+      const int grid = mapped_grid(n_keys, group, p.q_runs.total());
+      hipLaunchKernelGGL((step_bwd_dq_kernel<D, KB>), dim3(grid), dim3(256), LDS, stream, p);
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
   }
   if (p.dk.ptr) {
     constexpr int BQ = 64;
     constexpr int LDS = 2 * (2 * BQ * (2 * D + 16) + 2 * BQ * 4) + 4 * (BQ / 32) * 2 * 64 * 16;
-    const int grid = mapped_grid(n_keys, 1, (p.sk + 127) / 128);
-    hipLaunchKernelGGL((step_bwd_dkdv_kernel<D, BQ>), dim3(grid), dim3(512), LDS, stream, p);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    p.k_runs = nonempty_runs(p.mask, p.sq, p.sk, 128, false);
+    if (p.k_runs.total() < (p.sk + 127) / 128) {
+      if (!p.acc_dk) e = launch_zero_tensor(p.dk, p.batch, p.sk, p.kv_heads, p.head_dim, stream);
+      if (e == hipSuccess && !p.acc_dv) e = launch_zero_tensor(p.dv, p.batch, p.sk, p.kv_heads, p.head_dim, stream);
+      if (e != hipSuccess) return e;
+    }
+    if (p.k_runs.total() > 0) {
+      const int grid = mapped_grid(n_keys, 1, p.k_runs.total());
+      hipLaunchKernelGGL((step_bwd_dkdv_kernel<D, BQ>), dim3(grid), dim3(512), LDS, stream, p);
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
   }
   return hipSuccess;
 }

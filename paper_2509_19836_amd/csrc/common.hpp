@@ -55,20 +55,20 @@ struct RowvecDev {
   int64_t sb, sh;
 };
 
-__device__ __forceinline__ int seg_position(int row, int nseg, int seg_len, const int32_t* seg_pos, int stride) {
+__host__ __device__ __forceinline__ int seg_position(int row, int nseg, int seg_len, const int32_t* seg_pos, int stride) {
   int s = (nseg > 1 && row >= seg_len) ? 1 : 0;
   return seg_pos[s] + (row - s * seg_len) * stride;
 }
 
 // min / max position over local rows [row0, row1), row1 > row0
-__device__ __forceinline__ void range_minmax(int row0, int row1, int nseg, int seg_len, const int32_t* seg_pos,
+__host__ __device__ __forceinline__ void range_minmax(int row0, int row1, int nseg, int seg_len, const int32_t* seg_pos,
                                              int stride, int& lo, int& hi) {
   int last = row1 - 1;
   if (nseg > 1 && row0 < seg_len && last >= seg_len) {
     int lo0 = seg_pos[0] + row0 * stride, hi0 = seg_pos[0] + (seg_len - 1) * stride;
     int lo1 = seg_pos[1], hi1 = seg_pos[1] + (last - seg_len) * stride;
-    lo = min(lo0, lo1);
-    hi = max(hi0, hi1);
+    lo = lo0 < lo1 ? lo0 : lo1;
+    hi = hi0 > hi1 ? hi0 : hi1;
   } else {
     lo = seg_position(row0, nseg, seg_len, seg_pos, stride);
     hi = seg_position(last, nseg, seg_len, seg_pos, stride);
@@ -78,7 +78,7 @@ __device__ __forceinline__ void range_minmax(int row0, int row1, int nseg, int s
 // Classify the block of query rows [q0, q1) against key rows [k0, k1) (both already clipped to the
 // chunk).  PARTIAL = needs the per-element predicate: the mask edge crosses the block, or the caller
 // says so because the register tile also covers rows beyond the end of a chunk.
-__device__ __forceinline__ int classify(const MaskDev& mk, int q0, int q1, int k0, int k1, bool ragged) {
+__host__ __device__ __forceinline__ int classify(const MaskDev& mk, int q0, int q1, int k0, int k1, bool ragged) {
   if (k1 <= k0 || q1 <= q0) return TILE_SKIP;
   if (!mk.causal) return ragged ? TILE_PARTIAL : TILE_FULL;
   int qlo, qhi, klo, khi;
@@ -157,9 +157,11 @@ __device__ __forceinline__ float half_swap(float x) {
   return __shfl_xor(x, 32, 64);
 }
 
-// Stage a [ROWS x D] bf16 tile: global (row-major, row stride `ss` elements, rows clamped to
-// [0, nrows-1]) -> registers -> LDS, by THREADS threads.  Split in two so the loads can be issued before
-// the compute they overlap with.
+// Stage a [ROWS x D] bf16 tile: global (row-major, row stride `ss` elements) -> registers -> LDS,
+// by THREADS threads.  Split in two so the loads can be issued before the compute they overlap
+// with.  The per-lane part of the address is one 32-bit element offset computed once; the
+// per-tile and per-pass parts are wave-uniform, so a load costs no vector arithmetic.  Tiles that
+// reach past the last row take a slower path that clamps row indices instead.
 template <int D, int ROWS, int THREADS = 256>
 struct TileStager {
   static constexpr int CPR = D / 8;              // 16-byte chunks per row
@@ -168,21 +170,33 @@ struct TileStager {
   static constexpr int PITCH = 2 * D + 16;
   static_assert(ROWS % RPP == 0, "tile rows must be a multiple of rows per pass");
   u32x4 regs[PASSES];
+  uint32_t lane_off;    // (tid / CPR) * ss + (tid % CPR) * 8, elements
+  uint32_t lds_off[PASSES];
 
-  __device__ __forceinline__ void load(const __bf16* base, int64_t ss, int row0, int nrows, int tid) {
-    const int c = tid % CPR, rr = tid / CPR;
+  __device__ __forceinline__ void init(int64_t ss, int tid) {
+    lane_off = (uint32_t)(tid / CPR) * (uint32_t)ss + (uint32_t)(tid % CPR) * 8u;
 #pragma unroll
-    for (int i = 0; i < PASSES; ++i) {
-      int row = min(row0 + rr + i * RPP, nrows - 1);
-      regs[i] = *reinterpret_cast<const u32x4*>(base + (int64_t)row * ss + c * 8);
+    for (int i = 0; i < PASSES; ++i) lds_off[i] = lds_row(tid / CPR + i * RPP) * PITCH + (tid % CPR) * 16;
+  }
+  // base: first row of the tensor slice; row0: first tile row; nrows: rows in the slice (> row0)
+  __device__ __forceinline__ void load(const __bf16* base, int64_t ss, int row0, int nrows, int tid) {
+    if (row0 + ROWS <= nrows) {
+      const __bf16* tile = base + (int64_t)row0 * ss;    // uniform
+#pragma unroll
+      for (int i = 0; i < PASSES; ++i)
+        regs[i] = *reinterpret_cast<const u32x4*>(tile + (int64_t)i * RPP * ss + lane_off);
+    } else {
+      const int c = tid % CPR, rr = tid / CPR;
+#pragma unroll
+      for (int i = 0; i < PASSES; ++i) {
+        int row = min(row0 + rr + i * RPP, nrows - 1);
+        regs[i] = *reinterpret_cast<const u32x4*>(base + (int64_t)row * ss + c * 8);
+      }
     }
   }
-  __device__ __forceinline__ void store(char* tile, int tid) const {
-    const int c = tid % CPR, rr = tid / CPR;
+  __device__ __forceinline__ void store(char* tile) const {
 #pragma unroll
-    for (int i = 0; i < PASSES; ++i) {
-      *reinterpret_cast<u32x4*>(tile + lds_row(rr + i * RPP) * PITCH + c * 16) = regs[i];
-    }
+    for (int i = 0; i < PASSES; ++i) *reinterpret_cast<u32x4*>(tile + lds_off[i]) = regs[i];
   }
 };
 
@@ -207,6 +221,29 @@ __device__ __forceinline__ void gemm_rows(const char* tile, int row0, const bf16
     }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma32(a[ks][nb], breg[ks], acc[nb]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// Two row-wise GEMMs sharing the row block, interleaved so consecutive MFMAs alternate between the
+// two accumulators:  acc0 += rows(tile0) * b0,  acc1 += rows(tile1) * b1.
+template <int PITCH, int DK, int PRE>
+__device__ __forceinline__ void gemm_rows_pair(const char* tile0, const char* tile1, int row0, const bf16x8 (&b0)[DK],
+                                               const bf16x8 (&b1)[DK], f32x16& acc0, f32x16& acc1, int r, int h) {
+  bf16x8 a0[DK], a1[DK];
+#pragma unroll
+  for (int ks = 0; ks < PRE && ks < DK; ++ks) {
+    a0[ks] = lds_rows_operand<PITCH>(tile0, row0, ks * 16, r, h);
+    a1[ks] = lds_rows_operand<PITCH>(tile1, row0, ks * 16, r, h);
+  }
+#pragma unroll
+  for (int ks = 0; ks < DK; ++ks) {
+    if (ks + PRE < DK) {
+      a0[ks + PRE] = lds_rows_operand<PITCH>(tile0, row0, (ks + PRE) * 16, r, h);
+      a1[ks + PRE] = lds_rows_operand<PITCH>(tile1, row0, (ks + PRE) * 16, r, h);
+    }
+    acc0 = mfma32(a0[ks], b0[ks], acc0);
+    acc1 = mfma32(a1[ks], b1[ks], acc1);
     __builtin_amdgcn_sched_barrier(0);
   }
 }
@@ -260,5 +297,14 @@ __device__ __forceinline__ BlockMap map_block(int n, int n_keys, int group, int 
   return m;
 }
 inline int mapped_grid(int n_keys, int group, int tiles) { return 8 * ((n_keys + 7) / 8) * group * tiles; }
+
+// The tiles of an axis that have any visible pair, as up to two runs of consecutive tile indices
+// (a causal mask over one- or two-segment chunks never needs more).  Only these are launched: an
+// empty work-group costs a dispatch slot, and many of them in a row starve the other CUs.
+struct TileRuns {
+  int32_t start[2], len[2];
+  __host__ __device__ int total() const { return len[0] + len[1]; }
+  __host__ __device__ int tile_of(int i) const { return i < len[0] ? start[0] + i : start[1] + (i - len[0]); }
+};
 
 }  // namespace burst

@@ -13,6 +13,7 @@ struct FwdParams {
   int32_t sq, sk;
   float scale;
   MaskDev mask;
+  TileRuns q_runs;      // query tiles with work (filled by the launcher)
   TensorDev q, k, v;
   TensorDev o_part;     // ptr == nullptr: not requested
   RowvecDev lse_part;
@@ -25,6 +26,7 @@ struct BwdParams {
   int32_t sq, sk;
   float scale;
   MaskDev mask;
+  TileRuns q_runs, k_runs;   // query / key tiles with work (filled by the launcher)
   TensorDev q, k, v, d_o;
   RowvecDev lse, d;
   TensorDev dq, dk, dv;   // fp32; ptr == nullptr: skip
@@ -42,6 +44,31 @@ struct PreParams {
   TensorDev o, d_o;
   RowvecDev d;
 };
+
+// Runs of non-empty tiles along the query axis (each tile against the whole key chunk) or along
+// the key axis (each tile against the whole query chunk); the same classification the kernels use.
+inline TileRuns nonempty_runs(const MaskDev& mk, int sq, int sk, int tile_rows, bool q_axis) {
+  const int rows = q_axis ? sq : sk;
+  const int n = (rows + tile_rows - 1) / tile_rows;
+  TileRuns tr{{0, 0}, {0, 0}};
+  int nruns = 0;
+  bool in_run = false;
+  for (int t = 0; t < n; ++t) {
+    const int r0 = t * tile_rows, r1 = r0 + tile_rows < rows ? r0 + tile_rows : rows;
+    const int cls = q_axis ? classify(mk, r0, r1, 0, sk, false) : classify(mk, 0, sq, r0, r1, false);
+    if (cls == TILE_SKIP) {
+      in_run = false;
+      continue;
+    }
+    if (!in_run) {
+      if (nruns == 2) return TileRuns{{0, 0}, {n, 0}};   // more than two runs: launch every tile
+      tr.start[nruns++] = t;
+      in_run = true;
+    }
+    ++tr.len[nruns - 1];
+  }
+  return tr;
+}
 
 hipError_t launch_step_fwd(const FwdParams& p, hipStream_t stream);
 hipError_t launch_step_bwd(const BwdParams& p, hipStream_t stream);
