@@ -1,0 +1,115 @@
+"""Parity at the benchmark's full size and launch configuration (config 2: 32 heads, head_dim 128,
+16384-row query chunk against a 16384-row KV shard, zigzag positions of device 3 of 8).  The fp64
+oracle cannot do 10^12 flop exhaustively, so it computes, one by one, quantities that are exact
+given the step's inputs: whole sampled query rows (O, Lse, dQ are row-local once K and V are
+given) and whole sampled key rows (dK, dV are column-local once Q, dO, Lse and D are given)."""
+import numpy as np
+import pytest
+
+from oracle import burst_oracle as oc
+from paper_2509_19836_amd import workloads as wl
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_rows(n, seg, rng, extra=24):
+    edges = [0, 1, 31, 32, 63, 64, 127, 128, seg - 1, seg, seg + 1, seg + 127, seg + 128, n - 129, n - 128, n - 2, n - 1]
+    rows = set(e for e in edges if 0 <= e < n)
+    rows.update(int(x) for x in rng.integers(0, n, extra))
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+@pytest.mark.parametrize("shard_j", [3, 1, 5])
+def test_config2_step_sampled_rows(lib, shard_j):
+    import torch
+    w = wl.WORKLOADS[2]
+    G, N, i = w.shards, w.seq, 3
+    B, n, Hq, Hkv, d = w.batch, w.shard_tokens, w.q_heads, w.kv_heads, w.head_dim
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(wl.BASE_SEED + 200 + shard_j)
+    draw = lambda heads: torch.randn(B, n, heads, d, device="cuda", generator=gen).to(torch.bfloat16)
+    q, do, k, v = draw(Hq), draw(Hq), draw(Hkv), draw(Hkv)
+    mask = lib.burst_attn_fill_zigzag_mask(i, shard_j, G, N)
+    qpos, kpos = hp.mask_positions(mask, "q"), hp.mask_positions(mask, "k")
+    assert (qpos == oc.zigzag_positions(i, G, N)).all() and (kpos == oc.zigzag_positions(shard_j, G, N)).all()
+    shp = lib.shape(B, Hq, Hkv, d, n, n, w.scale)
+    f32 = dict(device="cuda", dtype=torch.float32)
+    o_part = torch.empty(B, n, Hq, d, **f32)
+    lse_part = torch.empty(B, Hq, n, **f32)
+    lib.burst_attn_step_fwd(shp, mask, q, k, v, o_part=o_part, lse_part=lse_part)
+    # backward inputs as a longer ring would deliver them: a larger, finite Lse and some D
+    lse_in = torch.where(torch.isfinite(lse_part), lse_part + 0.5, torch.full_like(lse_part, 3.0))
+    d_in = torch.randn(B, Hq, n, device="cuda", generator=gen)
+    dq = torch.full((B, n, Hq, d), float("nan"), **f32)
+    dk = torch.full((B, n, Hkv, d), float("nan"), **f32)
+    dv = torch.full((B, n, Hkv, d), float("nan"), **f32)
+    lib.burst_attn_step_bwd(shp, mask, q, k, v, do, lse_in, d_in, dq=dq, dk=dk, dv=dv)
+    torch.cuda.synchronize()
+    assert torch.isfinite(dq).all() and torch.isfinite(dk).all() and torch.isfinite(dv).all()
+
+    rng = np.random.Generator(np.random.PCG64(wl.BASE_SEED + 300 + shard_j))
+    rows = _sample_rows(n, n // 2, rng)
+    cols = _sample_rows(n, n // 2, rng)
+    to64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+    for head in (0, Hq - 1):
+        Qh, dOh, Kh, Vh = to64(q[0, :, head]), to64(do[0, :, head]), to64(k[0, :, head]), to64(v[0, :, head])
+        lse_h, d_h = to64(lse_in[0, head]), to64(d_in[0, head])
+        # whole query rows
+        vis_r = oc.visibility(qpos[rows], kpos, True)
+        O_ref, lse_ref = oc.step_fwd(Qh[rows], Kh, Vh, w.scale, vis_r)
+        o_scale = np.abs(to64(o_part[0, :, head])).max()
+        assert np.abs(to64(o_part[0, :, head])[rows] - O_ref).max() <= hp.REL_TOL * o_scale
+        assert hp.lse_err(to64(lse_part[0, head])[rows], lse_ref) <= hp.LSE_TOL
+        dQ_ref, _, _ = oc.step_bwd(Qh[rows], Kh, Vh, dOh[rows], lse_h[rows], d_h[rows], w.scale, vis_r)
+        dq_scale = np.abs(to64(dq[0, :, head])).max()
+        assert np.abs(to64(dq[0, :, head])[rows] - dQ_ref).max() <= hp.REL_TOL * dq_scale
+        # whole key rows
+        vis_c = oc.visibility(qpos, kpos[cols], True)
+        _, dK_ref, dV_ref = oc.step_bwd(Qh, Kh[cols], Vh[cols], dOh, lse_h, d_h, w.scale, vis_c)
+        dk_scale, dv_scale = np.abs(to64(dk[0, :, head])).max(), np.abs(to64(dv[0, :, head])).max()
+        assert np.abs(to64(dk[0, :, head])[cols] - dK_ref).max() <= hp.REL_TOL * dk_scale
+        assert np.abs(to64(dv[0, :, head])[cols] - dV_ref).max() <= hp.REL_TOL * dv_scale
+        # rows / columns the mask empties entirely must be exactly (0, -inf) / 0
+        dead_r = ~vis_r.any(axis=1)
+        assert (to64(o_part[0, :, head])[rows][dead_r] == 0).all()
+        assert (to64(dq[0, :, head])[rows][dead_r] == 0).all()
+        dead_c = ~vis_c.any(axis=0)
+        assert (to64(dk[0, :, head])[cols][dead_c] == 0).all() and (to64(dv[0, :, head])[cols][dead_c] == 0).all()
+
+
+def test_gqa_full_size_heads_group_reduction(lib):
+    """Config 3's grouping (64 query heads on 8 KV heads, head_dim 128) at a 4096-row shard: dK / dV of
+    one KV head against the oracle summed over its 8 query heads, on sampled key rows."""
+    import torch
+    B, n, Hq, Hkv, d, G, i, j = 1, 4096, 64, 8, 128, 8, 3, 3
+    N = n * G
+    scale = 1.0 / np.sqrt(d)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(wl.BASE_SEED + 303)
+    draw = lambda heads: torch.randn(B, n, heads, d, device="cuda", generator=gen).to(torch.bfloat16)
+    q, do, k, v = draw(Hq), draw(Hq), draw(Hkv), draw(Hkv)
+    mask = lib.burst_attn_fill_zigzag_mask(i, j, G, N)
+    qpos, kpos = hp.mask_positions(mask, "q"), hp.mask_positions(mask, "k")
+    shp = lib.shape(B, Hq, Hkv, d, n, n, scale)
+    f32 = dict(device="cuda", dtype=torch.float32)
+    lse_in = torch.full((B, Hq, n), 4.0, **f32) + torch.rand(B, Hq, n, device="cuda", generator=gen)
+    d_in = torch.randn(B, Hq, n, device="cuda", generator=gen)
+    dk = torch.empty(B, n, Hkv, d, **f32)
+    dv = torch.empty(B, n, Hkv, d, **f32)
+    lib.burst_attn_step_bwd(shp, mask, q, k, v, do, lse_in, d_in, dk=dk, dv=dv)
+    torch.cuda.synchronize()
+    rng = np.random.Generator(np.random.PCG64(wl.BASE_SEED + 304))
+    cols = _sample_rows(n, n // 2, rng, extra=8)
+    to64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+    g = 5
+    dK_ref = np.zeros((cols.size, d))
+    dV_ref = np.zeros((cols.size, d))
+    vis_c = oc.visibility(qpos, kpos[cols], True)
+    for hq in range(g * 8, g * 8 + 8):
+        _, dk_h, dv_h = oc.step_bwd(to64(q[0, :, hq]), to64(k[0, :, g])[cols], to64(v[0, :, g])[cols], to64(do[0, :, hq]),
+                                    to64(lse_in[0, hq]), to64(d_in[0, hq]), scale, vis_c)
+        dK_ref += dk_h
+        dV_ref += dv_h
+    assert np.abs(to64(dk[0, :, g])[cols] - dK_ref).max() <= hp.REL_TOL * np.abs(to64(dk[0, :, g])).max()
+    assert np.abs(to64(dv[0, :, g])[cols] - dV_ref).max() <= hp.REL_TOL * np.abs(to64(dv[0, :, g])).max()
