@@ -201,14 +201,14 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
     stage_do.load((const __bf16*)p.d_o.ptr + b * p.d_o.sb + hq * p.d_o.sh, p.d_o.ss, q0, sq, tid);
     if (tid < 2 * BQ) {
       const int rr = min(q0 + (tid % BQ), sq - 1);
-      stage_row = (tid < BQ) ? lse_to_log2(p.lse.ptr[b * p.lse.sb + hq * p.lse.sh + rr])
-                             : p.d.ptr[b * p.d.sb + hq * p.d.sh + rr];
+      // raw value only: converting here would wait for this load, and with it for the tile loads
+      stage_row = (tid < BQ) ? p.lse.ptr[b * p.lse.sb + hq * p.lse.sh + rr] : p.d.ptr[b * p.d.sb + hq * p.d.sh + rr];
     }
   };
   auto commit = [&](char* dst) {
     stage_q.store(dst);
     stage_do.store(dst + TILE);
-    if (tid < 2 * BQ) reinterpret_cast<float*>(dst + 2 * TILE)[tid] = stage_row;
+    if (tid < 2 * BQ) reinterpret_cast<float*>(dst + 2 * TILE)[tid] = tid < BQ ? lse_to_log2(stage_row) : stage_row;
   };
 
   wait_global_loads();
