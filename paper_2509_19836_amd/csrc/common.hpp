@@ -200,13 +200,21 @@ struct TileStager {
   }
 };
 
-// acc[nb] += A_nb * B for NB row blocks of an LDS tile: A_nb = tile rows row0 + 32*nb .. +31 (all D
+struct NoHook {
+  __device__ __forceinline__ void operator()(int) const {}
+};
+
+// acc[nb] (+)= A_nb * B for NB row blocks of an LDS tile: A_nb = tile rows row0 + 32*nb .. +31 (all D
 // columns, read row-wise), B = DK register operands.  The k-step is the outer loop so consecutive
 // MFMAs hit different accumulators, and LDS operands are fetched PRE k-steps ahead of their use;
 // the scheduling fences keep the compiler from hoisting more (registers) or less (latency).
-template <int PITCH, int NB, int DK, int PRE>
+// ZERO: the accumulators start from 0 (first MFMA takes the constant, no register clearing).
+// hook(ks) runs after the MFMAs of k-step ks, inside the same scheduling region: independent
+// vector work placed there issues while the matrix pipe is busy.
+template <int PITCH, int NB, int DK, int PRE, bool ZERO = false, class Hook = NoHook>
 __device__ __forceinline__ void gemm_rows(const char* tile, int row0, const bf16x8 (&breg)[DK], f32x16 (&acc)[NB],
-                                          int r, int h) {
+                                          int r, int h, Hook&& hook = Hook()) {
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   bf16x8 a[DK][NB];
 #pragma unroll
   for (int ks = 0; ks < PRE && ks < DK; ++ks)
@@ -220,7 +228,8 @@ __device__ __forceinline__ void gemm_rows(const char* tile, int row0, const bf16
         a[ks + PRE][nb] = lds_rows_operand<PITCH>(tile, row0 + 32 * nb, (ks + PRE) * 16, r, h);
     }
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma32(a[ks][nb], breg[ks], acc[nb]);
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma32(a[ks][nb], breg[ks], (ZERO && ks == 0) ? zero : acc[nb]);
+    hook(ks);
     __builtin_amdgcn_sched_barrier(0);
   }
 }
@@ -251,22 +260,20 @@ __device__ __forceinline__ void gemm_rows_pair(const char* tile0, const char* ti
 // acc[db] += A_db,c * b[c]: A = LDS tile read column-wise (columns 32*db .. +31, rows
 // row0 + 16*c .. +15 in packed-accumulator order), b[c] = packed register operands, c < NC.
 // One step = one 16-row chunk across all DB accumulators; operands fetched PRE steps ahead.
-template <int PITCH, int DB, int NC, int PRE>
+template <int PITCH, int DB, int NC, int PRE, class Hook = NoHook>
 __device__ __forceinline__ void gemm_cols(const char* tile, int row0, const bf16x8 (&b)[NC], f32x16 (&acc)[DB],
-                                          int lane) {
-  bf16x8 a[NC][DB];
+                                          int lane, Hook&& hook = Hook()) {
+  // operands in use order: i = c * DB + db; fetched AHEAD operands before use
+  constexpr int N = NC * DB, AHEAD = PRE * DB < 3 ? PRE * DB : 3;
+  bf16x8 a[N];
 #pragma unroll
-  for (int c = 0; c < PRE && c < NC; ++c)
+  for (int i = 0; i < AHEAD && i < N; ++i) a[i] = lds_cols_operand<PITCH>(tile, row0 + 16 * (i / DB), (i % DB) * 32, lane);
 #pragma unroll
-    for (int db = 0; db < DB; ++db) a[c][db] = lds_cols_operand<PITCH>(tile, row0 + 16 * c, db * 32, lane);
-#pragma unroll
-  for (int c = 0; c < NC; ++c) {
-    if (c + PRE < NC) {
-#pragma unroll
-      for (int db = 0; db < DB; ++db) a[c + PRE][db] = lds_cols_operand<PITCH>(tile, row0 + 16 * (c + PRE), db * 32, lane);
-    }
-#pragma unroll
-    for (int db = 0; db < DB; ++db) acc[db] = mfma32(a[c][db], b[c], acc[db]);
+  for (int i = 0; i < N; ++i) {
+    if (i + AHEAD < N)
+      a[i + AHEAD] = lds_cols_operand<PITCH>(tile, row0 + 16 * ((i + AHEAD) / DB), ((i + AHEAD) % DB) * 32, lane);
+    acc[i % DB] = mfma32(a[i], b[i / DB], acc[i % DB]);
+    if (i % DB == DB - 1) hook(i / DB);
     __builtin_amdgcn_sched_barrier(0);
   }
 }

@@ -85,11 +85,7 @@ __global__ __launch_bounds__(256, 2) void step_fwd_kernel(FwdParams p) {
     const int cls = classify(mk, q_w0, q_w1, t * BK, min(t * BK + BK, sk), t * BK + BK > sk);   // wave-uniform
     if (cls != TILE_SKIP) {
       f32x16 s[KB];
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
-      gemm_rows<PITCH, KB, DK, 2>(kt, 0, qreg, s, r, h);
+      gemm_rows<PITCH, KB, DK, 2, true>(kt, 0, qreg, s, r, h);
       if (cls == TILE_PARTIAL) {
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) mask_tile<true>(s[kb], mk, t * BK + kb * 32 + 4 * h, sk, qpos);
@@ -114,21 +110,33 @@ __global__ __launch_bounds__(256, 2) void step_fwd_kernel(FwdParams p) {
           for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
       }
       const float msub = (m_run == -INFINITY) ? 0.f : c * m_run;
-      float sum = 0.f;
-      bf16x8 pp[2 * KB];
+      // P = exp2(c S - c m) as packed bf16 pairs; the row sum is taken in fp32 before rounding (Lse
+      // must hold to 1e-3 also for rows with a handful of keys).  The exponentials of key block kb+1 are issued between the MFMAs of
+      // key block kb's PV product, so the vector ALU works while the matrix pipe is busy.
+      typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+      uint32_t ppw[KB][8];
+      auto exp_pairs = [&](int kb, int w0, int nw) {
+#pragma unroll
+        for (int w = w0; w < w0 + nw; ++w) {
+          const float e0 = __builtin_amdgcn_exp2f(c * s[kb][2 * w] - msub);
+          const float e1 = __builtin_amdgcn_exp2f(c * s[kb][2 * w + 1] - msub);
+          const bf16x2 pr = {(__bf16)e0, (__bf16)e1};
+          ppw[kb][w] = __builtin_bit_cast(uint32_t, pr);
+          l_run += e0 + e1;
+        }
+      };
+      exp_pairs(0, 0, 8);
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float e = __builtin_amdgcn_exp2f(c * s[kb][v] - msub);
-          s[kb][v] = e;
-          sum += e;
+        const u32x4 w_lo = {ppw[kb][0], ppw[kb][1], ppw[kb][2], ppw[kb][3]};
+        const u32x4 w_hi = {ppw[kb][4], ppw[kb][5], ppw[kb][6], ppw[kb][7]};
+        const bf16x8 pp[2] = {__builtin_bit_cast(bf16x8, w_lo), __builtin_bit_cast(bf16x8, w_hi)};
+        if (kb + 1 < KB) {
+          gemm_cols<PITCH, DB, 2, 1>(vt, kb * 32, pp, o, lane, [&](int c2) { exp_pairs(kb + 1, 4 * c2, 4); });
+        } else {
+          gemm_cols<PITCH, DB, 2, 1>(vt, kb * 32, pp, o, lane);
         }
-        pp[2 * kb] = pack8(s[kb], 0);
-        pp[2 * kb + 1] = pack8(s[kb], 1);
       }
-      l_run += sum;
-      gemm_cols<PITCH, DB, 2 * KB, 1>(vt, 0, pp, o, lane);
     }
     if (tn < n_tiles) {
       char* nk = smem + (buf ^ 1) * 2 * TILE;
