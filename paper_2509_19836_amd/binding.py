@@ -11,7 +11,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libburstattn.so")
+LIB_PATH = os.environ.get("BURST_LIB_PATH", os.path.join(_HERE, "libburstattn.so"))   # override: another build
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(

@@ -12,10 +12,10 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffast-math", "
          "-Wno-unused-command-line-argument"]
 
 
-def build(verbose=False, extra_flags=()):
+def build(verbose=False, extra_flags=(), out_path=None, tag=""):
     """Compile every source to an object (in parallel) and link the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objdir = os.path.join(HERE, "_build")
+    objdir = os.path.join(HERE, "_build" + tag)
     os.makedirs(objdir, exist_ok=True)
     procs = []
     for src in SOURCES:
@@ -33,11 +33,11 @@ def build(verbose=False, extra_flags=()):
         if verbose and out.strip():
             print(out)
         objs.append(obj)
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out_path or LIB_PATH]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stdout}")
-    return LIB_PATH
+    return out_path or LIB_PATH
 
 
 if __name__ == "__main__":

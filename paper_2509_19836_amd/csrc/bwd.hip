@@ -21,6 +21,11 @@
 
 namespace burst {
 
+#ifndef BURST_DQ_BQ
+#define BURST_DQ_BQ 256
+#endif
+constexpr int kDqBQ = BURST_DQ_BQ;   // query rows per work-group of the dQ kernel: 32 per wave
+
 // lse in log2 units, with -inf mapped to +inf so that exp2(x - lse2) = 0 for a dead row
 __device__ __forceinline__ float lse_to_log2(float lse) { return lse == -INFINITY ? INFINITY : lse * kLog2e; }
 
@@ -30,9 +35,9 @@ __device__ __forceinline__ void zero16(f32x16& x) {
 }
 
 // ---------------------------------------------------------------------------------------------
-template <int D, int KB>
-__global__ __launch_bounds__(256, 2) void step_bwd_dq_kernel(BwdParams p) {
-  constexpr int BK = 32 * KB, DK = D / 16, DB = D / 32, BQ = 128;
+template <int D, int KB, int NW>
+__global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_bwd_dq_kernel(BwdParams p) {
+  constexpr int BK = 32 * KB, DK = D / 16, DB = D / 32, BQ = 32 * NW, NT = 64 * NW;
   constexpr int PITCH = 2 * D + 16;
   constexpr int TILE = BK * PITCH;
   extern __shared__ __attribute__((aligned(16))) char smem[];  // [2 buffers][K tile, V tile]
@@ -77,7 +82,7 @@ __global__ __launch_bounds__(256, 2) void step_bwd_dq_kernel(BwdParams p) {
     return t;
   };
 
-  TileStager<D, BK> stage_k, stage_v;
+  TileStager<D, BK, NT> stage_k, stage_v;
   stage_k.init(p.k.ss, tid);
   stage_v.init(p.v.ss, tid);
   wait_global_loads();
@@ -105,7 +110,7 @@ __global__ __launch_bounds__(256, 2) void step_bwd_dq_kernel(BwdParams p) {
         f32x16 sd[2];   // S^T and dP^T of this key block: two independent accumulator chains
         zero16(sd[0]);
         zero16(sd[1]);
-        gemm_rows_pair<PITCH, DK, 2>(kt, vt, kb * 32, qreg, doreg, sd[0], sd[1], r, h);
+        gemm_rows_pair<PITCH, DK, kRowsAhead>(kt, vt, kb * 32, qreg, doreg, sd[0], sd[1], r, h);
         if (cls == TILE_PARTIAL) mask_tile<true>(sd[0], mk, t * BK + kb * 32 + 4 * h, sk, qpos);
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -113,7 +118,7 @@ __global__ __launch_bounds__(256, 2) void step_bwd_dq_kernel(BwdParams p) {
           sd[0][v] = pr * (sd[1][v] - dval);
         }
         bf16x8 ds[2] = {pack8(sd[0], 0), pack8(sd[0], 1)};
-        gemm_cols<PITCH, DB, 2, 1>(kt, kb * 32, ds, dq, lane);
+        gemm_cols<PITCH, DB, 2, kColsAhead>(kt, kb * 32, ds, dq, lane);
       }
     }
     if (tn < n_tiles) {
@@ -235,7 +240,7 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
         f32x16 s[QBK];
 #pragma unroll
         for (int qb = 0; qb < QBK; ++qb) zero16(s[qb]);
-        gemm_rows<PITCH, QBK, DK, 2>(qt_, 0, xreg, s, r, h);
+        gemm_rows<PITCH, QBK, DK, kRowsAhead>(qt_, 0, xreg, s, r, h);
 #pragma unroll
         for (int qb = 0; qb < QBK; ++qb) {
           if (cls == TILE_PARTIAL) mask_tile<false>(s[qb], mk, q0 + qb * 32 + 4 * h, sq, kpos);
@@ -252,13 +257,13 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
         }
       }
       __syncthreads();
-      if (cls != TILE_SKIP) gemm_cols<PITCH, DB, 2 * QBK, 1>(dot_, 0, pk, acc, lane);
+      if (cls != TILE_SKIP) gemm_cols<PITCH, DB, 2 * QBK, kColsAhead>(dot_, 0, pk, acc, lane);
     } else {
       f32x16 dp[QBK];
       if (cls != TILE_SKIP) {
 #pragma unroll
         for (int qb = 0; qb < QBK; ++qb) zero16(dp[qb]);
-        gemm_rows<PITCH, QBK, DK, 2>(dot_, 0, xreg, dp, r, h);
+        gemm_rows<PITCH, QBK, DK, kRowsAhead>(dot_, 0, xreg, dp, r, h);
       }
       __syncthreads();
       if (cls != TILE_SKIP) {
@@ -280,7 +285,7 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
           dsp[2 * qb] = pack8(dp[qb], 0);
           dsp[2 * qb + 1] = pack8(dp[qb], 1);
         }
-        gemm_cols<PITCH, DB, 2 * QBK, 1>(qt_, 0, dsp, acc, lane);
+        gemm_cols<PITCH, DB, 2 * QBK, kColsAhead>(qt_, 0, dsp, acc, lane);
       }
     }
     if (itn < n_items) commit(smem + (buf ^ 1) * BUF);
@@ -326,15 +331,15 @@ static hipError_t launch_bwd_t(BwdParams p, hipStream_t stream) {
   if (p.dq.ptr) {
     constexpr int KB = 2;
     constexpr int LDS = 2 * 2 * 32 * KB * (2 * D + 16);
-    p.q_runs = nonempty_runs(p.mask, p.sq, p.sk, 128, true);
+    p.q_runs = nonempty_runs(p.mask, p.sq, p.sk, kDqBQ, true);
     // query tiles that see no key get no work-group: "=" must still leave zeros there
-    if (!p.acc_dq && p.q_runs.total() < (p.sq + 127) / 128) {
+    if (!p.acc_dq && p.q_runs.total() < (p.sq + kDqBQ - 1) / kDqBQ) {
       e = launch_zero_tensor(p.dq, p.batch, p.sq, p.q_heads, p.head_dim, stream);
       if (e != hipSuccess) return e;
     }
     if (p.q_runs.total() > 0) {
       const int grid = mapped_grid(n_keys, group, p.q_runs.total());
-      hipLaunchKernelGGL((step_bwd_dq_kernel<D, KB>), dim3(grid), dim3(256), LDS, stream, p);
+      hipLaunchKernelGGL((step_bwd_dq_kernel<D, KB, kDqBQ / 32>), dim3(grid), dim3(2 * kDqBQ), LDS, stream, p);
       e = hipGetLastError();
       if (e != hipSuccess) return e;
     }

@@ -264,7 +264,7 @@ template <int PITCH, int DB, int NC, int PRE, class Hook = NoHook>
 __device__ __forceinline__ void gemm_cols(const char* tile, int row0, const bf16x8 (&b)[NC], f32x16 (&acc)[DB],
                                           int lane, Hook&& hook = Hook()) {
   // operands in use order: i = c * DB + db; fetched AHEAD operands before use
-  constexpr int N = NC * DB, AHEAD = PRE * DB < 3 ? PRE * DB : 3;
+  constexpr int N = NC * DB, AHEAD = PRE;   // PRE counts operands here
   bf16x8 a[N];
 #pragma unroll
   for (int i = 0; i < AHEAD && i < N; ++i) a[i] = lds_cols_operand<PITCH>(tile, row0 + 16 * (i / DB), (i % DB) * 32, lane);

@@ -14,9 +14,14 @@
 
 namespace burst {
 
-template <int D>
-__global__ __launch_bounds__(256, 2) void step_fwd_kernel(FwdParams p) {
-  constexpr int BK = 64, KB = BK / 32, DK = D / 16, DB = D / 32, BQ = 128;
+#ifndef BURST_FWD_BQ
+#define BURST_FWD_BQ 256
+#endif
+constexpr int kFwdBQ = BURST_FWD_BQ;   // query rows per work-group: 32 per wave
+
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdParams p) {
+  constexpr int BK = 64, KB = BK / 32, DK = D / 16, DB = D / 32, BQ = 32 * NW, NT = 64 * NW;
   constexpr int PITCH = 2 * D + 16;
   constexpr int TILE = BK * PITCH;
   extern __shared__ __attribute__((aligned(16))) char smem[];  // [2 buffers][K tile, V tile]
@@ -61,7 +66,7 @@ __global__ __launch_bounds__(256, 2) void step_fwd_kernel(FwdParams p) {
     return t;
   };
 
-  TileStager<D, BK> stage_k, stage_v;
+  TileStager<D, BK, NT> stage_k, stage_v;
   stage_k.init(p.k.ss, tid);
   stage_v.init(p.v.ss, tid);
   wait_global_loads();
@@ -85,7 +90,7 @@ __global__ __launch_bounds__(256, 2) void step_fwd_kernel(FwdParams p) {
     const int cls = classify(mk, q_w0, q_w1, t * BK, min(t * BK + BK, sk), t * BK + BK > sk);   // wave-uniform
     if (cls != TILE_SKIP) {
       f32x16 s[KB];
-      gemm_rows<PITCH, KB, DK, 2, true>(kt, 0, qreg, s, r, h);
+      gemm_rows<PITCH, KB, DK, kRowsAhead, true>(kt, 0, qreg, s, r, h);
       if (cls == TILE_PARTIAL) {
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) mask_tile<true>(s[kb], mk, t * BK + kb * 32 + 4 * h, sk, qpos);
@@ -132,9 +137,9 @@ __global__ __launch_bounds__(256, 2) void step_fwd_kernel(FwdParams p) {
         const u32x4 w_hi = {ppw[kb][4], ppw[kb][5], ppw[kb][6], ppw[kb][7]};
         const bf16x8 pp[2] = {__builtin_bit_cast(bf16x8, w_lo), __builtin_bit_cast(bf16x8, w_hi)};
         if (kb + 1 < KB) {
-          gemm_cols<PITCH, DB, 2, 1>(vt, kb * 32, pp, o, lane, [&](int c2) { exp_pairs(kb + 1, 4 * c2, 4); });
+          gemm_cols<PITCH, DB, 2, kColsAhead>(vt, kb * 32, pp, o, lane, [&](int c2) { exp_pairs(kb + 1, 4 * c2, 4); });
         } else {
-          gemm_cols<PITCH, DB, 2, 1>(vt, kb * 32, pp, o, lane);
+          gemm_cols<PITCH, DB, 2, kColsAhead>(vt, kb * 32, pp, o, lane);
         }
       }
     }
@@ -206,7 +211,7 @@ __global__ __launch_bounds__(256, 2) void step_fwd_kernel(FwdParams p) {
 // result for them is (0, -inf); the running state is left alone.
 __global__ __launch_bounds__(256) void fwd_fill_dead_rows_kernel(FwdParams p) {
   const int d4 = p.head_dim / 4;
-  const int n_tiles = (p.sq + 127) / 128;
+  const int n_tiles = (p.sq + kFwdBQ - 1) / kFwdBQ;
   const int64_t total = (int64_t)p.batch * p.sq * p.q_heads * d4;
   for (int64_t i = blockIdx.x * 256ll + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
     const int cc = i % d4;
@@ -215,7 +220,7 @@ __global__ __launch_bounds__(256) void fwd_fill_dead_rows_kernel(FwdParams p) {
     rest /= p.q_heads;
     const int row = rest % p.sq;
     const int b = rest / p.sq;
-    const int tile = row / 128;
+    const int tile = row / kFwdBQ;
     const bool covered = (tile >= p.q_runs.start[0] && tile < p.q_runs.start[0] + p.q_runs.len[0]) ||
                          (tile >= p.q_runs.start[1] && tile < p.q_runs.start[1] + p.q_runs.len[1]);
     if (covered || tile >= n_tiles) continue;
@@ -231,7 +236,7 @@ __global__ __launch_bounds__(256) void fwd_fill_dead_rows_kernel(FwdParams p) {
 
 template <int D>
 static hipError_t launch_fwd_t(FwdParams p, hipStream_t stream) {
-  constexpr int BQ = 128;
+  constexpr int BQ = kFwdBQ;
   constexpr int LDS = 2 * 2 * 64 * (2 * D + 16);
   p.q_runs = nonempty_runs(p.mask, p.sq, p.sk, BQ, true);
   const int n_tiles = (p.sq + BQ - 1) / BQ;
@@ -244,7 +249,7 @@ static hipError_t launch_fwd_t(FwdParams p, hipStream_t stream) {
   }
   if (p.q_runs.total() == 0) return hipSuccess;
   const int grid = mapped_grid(p.batch * p.kv_heads, p.q_heads / p.kv_heads, p.q_runs.total());
-  hipLaunchKernelGGL((step_fwd_kernel<D>), dim3(grid), dim3(256), LDS, stream, p);
+  hipLaunchKernelGGL((step_fwd_kernel<D, kFwdBQ / 32>), dim3(grid), dim3(2 * kFwdBQ), LDS, stream, p);
   return hipGetLastError();
 }
 

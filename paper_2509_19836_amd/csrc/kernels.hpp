@@ -8,6 +8,15 @@ namespace burst {
 // 2^kLazyLog2; exp2 arguments then stay <= kLazyLog2, far inside fp32 / bf16 range.
 constexpr float kLazyLog2 = 6.0f;
 
+// LDS operand prefetch distances: k-steps ahead for row-wise GEMMs, operands ahead for column-wise.
+#ifndef BURST_ROWS_AHEAD
+#define BURST_ROWS_AHEAD 2
+#endif
+#ifndef BURST_COLS_AHEAD
+#define BURST_COLS_AHEAD 3
+#endif
+constexpr int kRowsAhead = BURST_ROWS_AHEAD, kColsAhead = BURST_COLS_AHEAD;
+
 struct FwdParams {
   int32_t batch, q_heads, kv_heads, head_dim;
   int32_t sq, sk;
