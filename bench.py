@@ -148,6 +148,25 @@ def main():
         spans[name].append(a.elapsed_time(b))
     assert torch.isfinite(o_acc).all() and torch.isfinite(dq).all(), "non-finite result"
 
+    # Outside the timed region: (1) the matrix-core ceiling of this chip as clocked under load, with
+    # constant and with random register operands (real attention tiles are bounded by the latter: the
+    # chip lowers its clock when the MFMA inputs toggle); (2) one plain 1 GiB device copy, so that a
+    # counter profile of this command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by.
+    ceiling = {}
+    for name, rnd in (("constant_operands", 0), ("random_operands", 1)):
+        lib.burst_attn_mfma_probe(rnd, 20000)
+        a, b = ev(), ev()
+        a.record()
+        flops = lib.burst_attn_mfma_probe(rnd, 200000)
+        b.record()
+        torch.cuda.synchronize()
+        ceiling[name] = flops / (a.elapsed_time(b) * 1e-3) / 1e12
+    src = torch.empty(1 << 28, device="cuda", dtype=torch.float32)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
     ring_pairs = sum(pairs.values()) * B * Hq
     fl_fwd, fl_bwd = ring_pairs * 4 * d, ring_pairs * 10 * d
     ms_ring = total_s / args.steps * 1e3
@@ -174,6 +193,8 @@ def main():
         "fwd_tflops": round(fl_fwd / (fwd_ms * 1e-3) / 1e12, 2),
         "bwd_tflops": round(fl_bwd / (bwd_ms * 1e-3) / 1e12, 2),
         "kernel_ms": {k: round(v, 4) for k, v in avg.items()},
+        "mfma_ceiling_tflops": {k: round(v, 1) for k, v in ceiling.items()},
+        "pct_of_random_operand_mfma_ceiling": round(100 * value / ceiling["random_operands"], 2),
         "roofline": {"bound": "mfma", "kernel": "step_bwd_dkdv_kernel", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "traffic": None,

@@ -158,6 +158,15 @@ int burst_attn_fill_striped_mask(int32_t dev_i, int32_t shard_j, int32_t G, int6
  * unit (4*head_dim flop forward, 10*head_dim backward).  Returns -1 on an invalid mask. */
 int64_t burst_attn_visible_pairs(const burst_mask_t* mask);
 
+/* Diagnostic, not part of the attention path: enqueues `iterations` x 4 independent bf16 32x32x16
+ * MFMAs per wave on every SIMD (512 work-groups of 256 threads) with constant (0) or pseudo-random
+ * (1) register operands, and stores the flop count of the launch in *flops_out (host, optional).
+ * Timed by the caller with events, it gives the matrix-core ceiling of the chip as it is clocked under
+ * that load: dense attention tiles are bounded by the random-operand figure.  sink: optional device
+ * pointer to 4 bytes (never written in practice).  iterations in [1, 2^24]. */
+int burst_attn_mfma_probe(int32_t random_operands, int32_t iterations, float* sink, int64_t* flops_out,
+                          void* hip_stream);
+
 const char* burst_attn_status_string(int status);
 int burst_attn_last_hip_error(void);
 const char* burst_attn_version(void);

@@ -64,6 +64,8 @@ for _name in ("zigzag", "contiguous", "striped"):
     _f.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int32, _P(burst_mask_t)]
 _lib.burst_attn_visible_pairs.restype = C.c_int64
 _lib.burst_attn_visible_pairs.argtypes = [_P(burst_mask_t)]
+_lib.burst_attn_mfma_probe.restype = C.c_int
+_lib.burst_attn_mfma_probe.argtypes = [C.c_int32, C.c_int32, C.c_void_p, _P(C.c_int64), C.c_void_p]
 _lib.burst_attn_status_string.restype = C.c_char_p
 _lib.burst_attn_status_string.argtypes = [C.c_int]
 _lib.burst_attn_last_hip_error.restype = C.c_int
@@ -71,7 +73,7 @@ _lib.burst_attn_version.restype = C.c_char_p
 
 EXPORTS = ["burst_attn_step_fwd", "burst_attn_lse_merge", "burst_attn_preprocess_bwd", "burst_attn_step_bwd",
            "burst_attn_fill_zigzag_mask", "burst_attn_fill_contiguous_mask", "burst_attn_fill_striped_mask",
-           "burst_attn_visible_pairs", "burst_attn_status_string", "burst_attn_last_hip_error",
+           "burst_attn_visible_pairs", "burst_attn_mfma_probe", "burst_attn_status_string", "burst_attn_last_hip_error",
            "burst_attn_version"]
 
 
@@ -172,6 +174,13 @@ def burst_attn_step_bwd(shp, mask, q, k, v, d_o, lse, d, dq=None, dk=None, dv=No
     _check(_lib.burst_attn_step_bwd(C.byref(shp), _ref(mask), _ref(tensor(q)), _ref(tensor(k)), _ref(tensor(v)),
                                     _ref(tensor(d_o)), _ref(rowvec(lse)), _ref(rowvec(d)), _ref(tensor(dq)),
                                     _ref(tensor(dk)), _ref(tensor(dv)), accumulate_flags, _stream(stream)))
+
+
+def burst_attn_mfma_probe(random_operands, iterations, stream=None):
+    """Enqueue the MFMA ceiling probe; returns the flop count of the launch."""
+    flops = C.c_int64(0)
+    _check(_lib.burst_attn_mfma_probe(int(random_operands), iterations, None, C.byref(flops), _stream(stream)))
+    return flops.value
 
 
 def raw():

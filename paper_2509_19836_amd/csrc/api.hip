@@ -300,6 +300,13 @@ int64_t burst_attn_visible_pairs(const burst_mask_t* m) {
   return total;
 }
 
+int burst_attn_mfma_probe(int32_t random_operands, int32_t iterations, float* sink, int64_t* flops_out,
+                          void* hip_stream) {
+  if (iterations < 1 || iterations > (1 << 24)) return BURST_ERR_INVALID_ARG;
+  hipError_t e = launch_mfma_probe(sink, iterations, random_operands != 0, flops_out, (hipStream_t)hip_stream);
+  return e == hipSuccess ? BURST_OK : hip_fail(e);
+}
+
 const char* burst_attn_status_string(int status) {
   switch (status) {
     case BURST_OK: return "ok";

@@ -152,4 +152,48 @@ hipError_t launch_zero_tensor(const TensorDev& t, int32_t batch, int32_t rows, i
   return hipGetLastError();
 }
 
+// Diagnostic: back-to-back independent bf16 MFMAs from registers, two waves per SIMD on every CU.
+// With constant operands the chip holds its top clock; with random operands the same instruction
+// stream runs at the clock the power limit allows, which is the ceiling an attention kernel with
+// real data can reach.
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float* sink, int iters, int random_operands) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const uint32_t u = (threadIdx.x * 97u + e * 131u + blockIdx.x * 7u) * 2654435761u;
+    const uint16_t wa = 0x3c00u | ((u >> 9) & 0x83ffu), wb = 0x3c00u | ((u >> 3) & 0x83ffu);   // |x| in [0.0078, 2)
+    a[e] = random_operands ? __builtin_bit_cast(__bf16, wa) : (__bf16)1.0f;
+    b[e] = random_operands ? __builtin_bit_cast(__bf16, wb) : (__bf16)0.5f;
+  }
+  f32x16 c0, c1, c2, c3;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) c0[v] = c1[v] = c2[v] = c3[v] = 0.f;
+  for (int i = 0; i < iters; ++i) {
+    c0 = mfma32(a, b, c0);
+    c1 = mfma32(a, b, c1);
+    c2 = mfma32(a, b, c2);
+    c3 = mfma32(a, b, c3);
+    if ((i & 1023) == 1023) {   // keep the accumulators finite
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        c0[v] *= 1e-30f;
+        c1[v] *= 1e-30f;
+        c2[v] *= 1e-30f;
+        c3[v] *= 1e-30f;
+      }
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) s += c0[v] + c1[v] + c2[v] + c3[v];
+  if (sink && s == 12345.678f) sink[0] = s;   // never true in practice; keeps the loop alive
+}
+
+hipError_t launch_mfma_probe(float* sink, int iters, int random_operands, int64_t* flops, hipStream_t stream) {
+  const int blocks = 512;   // 256 CUs x 2 work-groups x 4 waves
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, stream, sink, iters, random_operands);
+  if (flops) *flops = (int64_t)blocks * 4 * iters * 4 * 32768;
+  return hipGetLastError();
+}
+
 }  // namespace burst

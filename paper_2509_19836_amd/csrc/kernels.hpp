@@ -85,6 +85,7 @@ hipError_t launch_lse_merge(const MergeParams& p, hipStream_t stream);
 hipError_t launch_preprocess_bwd(const PreParams& p, hipStream_t stream);
 // o_part = 0 / lse_part = -inf for a step with no key rows; zero-fill of fp32 gradients
 hipError_t launch_fill_empty_fwd(const FwdParams& p, hipStream_t stream);
+hipError_t launch_mfma_probe(float* sink, int iters, int random_operands, int64_t* flops, hipStream_t stream);
 hipError_t launch_zero_tensor(const TensorDev& t, int32_t batch, int32_t rows, int32_t heads, int32_t head_dim,
                               hipStream_t stream);
 
