@@ -43,7 +43,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_bwd_dq_kernel(B
   extern __shared__ __attribute__((aligned(16))) char smem[];  // [2 buffers][K tile, V tile]
 
   const int group = p.q_heads / p.kv_heads;
-  const BlockMap bm = map_block(blockIdx.x, p.batch * p.kv_heads, group, p.q_runs.total());
+  const BlockMap bm = map_block<true>(blockIdx.x, p.batch * p.kv_heads, group, p.q_runs.total());
   if (!bm.valid) return;
   const int b = bm.key / p.kv_heads, hk = bm.key - b * p.kv_heads, hq = hk * group + bm.head_in_group;
 
@@ -184,31 +184,37 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
 #pragma unroll
   for (int db = 0; db < DB; ++db) zero16(acc[db]);
 
-  // flattened walk over (query head of the group, query tile), skipping tiles the mask empties
-  const int q_tiles = (sq + BQ - 1) / BQ;
-  const int n_items = group * q_tiles;
-  auto next_item = [&](int it) {
-    while (it < n_items) {
-      int qt = it % q_tiles;
-      if (classify(mk, qt * BQ, min(qt * BQ + BQ, sq), k_blk0, k_blk1, false) != TILE_SKIP) break;
-      ++it;
-    }
-    return it;
-  };
+  // Position ranges of the work-group's 128 key rows and of this pair's 32: loop invariants of the
+  // tile classification.
+  int klo_blk, khi_blk, klo_w = 0, khi_w = 0;
+  range_minmax(k_blk0, k_blk1, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride, klo_blk, khi_blk);
+  const bool has_keys = k_w0 < k_w1;
+  if (has_keys) range_minmax(k_w0, k_w1, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride, klo_w, khi_w);
+
+  // Walk over (query head of the group, query tile that can see the key block), flattened so the
+  // double buffering runs across head boundaries.  Only counters and compares per step: the per-head
+  // base pointers change on a head switch, the tile index comes from the precomputed runs.
+  const TileRuns qr = visible_tiles<true, BQ>(mk, klo_blk, sq);
+  const int per_head = qr.total();
+  const int n_items = group * per_head;
 
   TileStager<D, BQ, NT> stage_q, stage_do;
   stage_q.init(p.q.ss, tid);
   stage_do.init(p.d_o.ss, tid);
   float stage_row = 0.f;   // threads [0, BQ): lse2 of a row; threads [BQ, 2*BQ): D of a row
-  auto issue = [&](int it) {
-    const int hq = hk * group + it / q_tiles, q0 = (it % q_tiles) * BQ;
-    stage_q.load((const __bf16*)p.q.ptr + b * p.q.sb + hq * p.q.sh, p.q.ss, q0, sq, tid);
-    stage_do.load((const __bf16*)p.d_o.ptr + b * p.d_o.sb + hq * p.d_o.sh, p.d_o.ss, q0, sq, tid);
-    if (tid < 2 * BQ) {
-      const int rr = min(q0 + (tid % BQ), sq - 1);
-      // raw value only: converting here would wait for this load, and with it for the tile loads
-      stage_row = (tid < BQ) ? p.lse.ptr[b * p.lse.sb + hq * p.lse.sh + rr] : p.d.ptr[b * p.d.sb + hq * p.d.sh + rr];
-    }
+  const __bf16 *q_head, *do_head;
+  const float* row_head;   // lse (threads < BQ) or D of the head being staged
+  auto set_head = [&](int g) {
+    const int hq = hk * group + g;
+    q_head = (const __bf16*)p.q.ptr + b * p.q.sb + hq * p.q.sh;
+    do_head = (const __bf16*)p.d_o.ptr + b * p.d_o.sb + hq * p.d_o.sh;
+    row_head = tid < BQ ? p.lse.ptr + b * p.lse.sb + hq * p.lse.sh : p.d.ptr + b * p.d.sb + hq * p.d.sh;
+  };
+  auto issue = [&](int q0) {
+    stage_q.load(q_head, p.q.ss, q0, sq, tid);
+    stage_do.load(do_head, p.d_o.ss, q0, sq, tid);
+    // raw value only: converting here would wait for this load, and with it for the tile loads
+    if (tid < 2 * BQ) stage_row = row_head[min(q0 + (tid & (BQ - 1)), sq - 1)];
   };
   auto commit = [&](char* dst) {
     stage_q.store(dst);
@@ -217,23 +223,33 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
   };
 
   wait_global_loads();
-  int it = next_item(0);
-  if (it < n_items) {
-    issue(it);
+  int idx = 0, head = 0;    // position of the NEXT item to stage: run index within the head, head of the group
+  set_head(0);
+  if (n_items > 0) {
+    issue(qr.tile_of(0) * BQ);
     commit(smem);
   }
   __syncthreads();
   int buf = 0;
-  while (it < n_items) {
-    const int itn = next_item(it + 1);
-    if (itn < n_items) issue(itn);
+  for (int it = 0; it < n_items; ++it) {
+    const int q0 = qr.tile_of(idx) * BQ;   // tile in LDS now
+    if (++idx == per_head) {
+      idx = 0;
+      if (++head < group) set_head(head);
+    }
+    const bool more = it + 1 < n_items;
+    if (more) issue(qr.tile_of(idx) * BQ);
     const char* qt_ = smem + buf * BUF;
     const char* dot_ = qt_ + TILE;
     const float* rowv = reinterpret_cast<const float*>(qt_ + 2 * TILE);
-    const int q0 = (it % q_tiles) * BQ;
     // Class of the whole query tile against this pair's 32 key rows (same for both waves of the
     // pair).  A tile the mask only partly empties is computed whole with the per-element predicate.
-    const int cls = classify(mk, q0, min(q0 + BQ, sq), k_w0, k_w1, q0 + BQ > sq);
+    int cls = TILE_SKIP;
+    if (has_keys) {
+      int qlo, qhi;
+      range_minmax(q0, min(q0 + BQ, sq), mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, qlo, qhi);
+      cls = classify_range<true>(mk, qlo, qhi, klo_w, khi_w, q0 + BQ > sq);
+    }
     if (ROLE == 0) {
       bf16x8 pk[2 * QBK];
       if (cls != TILE_SKIP) {
@@ -288,9 +304,8 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
         gemm_cols<PITCH, DB, 2 * QBK, kColsAhead>(qt_, 0, dsp, acc, lane);
       }
     }
-    if (itn < n_items) commit(smem + (buf ^ 1) * BUF);
+    if (more) commit(smem + (buf ^ 1) * BUF);
     __syncthreads();
-    it = itn;
     buf ^= 1;
   }
 
@@ -314,7 +329,7 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
 template <int D, int BQ>
 __global__ __launch_bounds__(512, 1) void step_bwd_dkdv_kernel(BwdParams p) {
   extern __shared__ __attribute__((aligned(16))) char smem[];   // [2][tile buffers], then the P hand-over area
-  const BlockMap bm = map_block(blockIdx.x, p.batch * p.kv_heads, 1, p.k_runs.total());
+  const BlockMap bm = map_block<false>(blockIdx.x, p.batch * p.kv_heads, 1, p.k_runs.total());
   if (!bm.valid) return;
   const int b = bm.key / p.kv_heads, hk = bm.key - b * p.kv_heads;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: the role branch is uniform

@@ -89,6 +89,18 @@ __host__ __device__ __forceinline__ int classify(const MaskDev& mk, int q0, int 
   return TILE_PARTIAL;
 }
 
+// Class of the row block whose positions span [lo, hi] against rows of the other axis spanning
+// [olo, ohi]; Q_ROWS says which side the block is on.  Same decisions as classify(), for callers
+// that keep the other side's range in registers.
+template <bool Q_ROWS>
+__host__ __device__ __forceinline__ int classify_range(const MaskDev& mk, int lo, int hi, int olo, int ohi, bool ragged) {
+  if (!mk.causal) return ragged ? TILE_PARTIAL : TILE_FULL;
+  const int qlo = Q_ROWS ? lo : olo, qhi = Q_ROWS ? hi : ohi, klo = Q_ROWS ? olo : lo, khi = Q_ROWS ? ohi : hi;
+  if (qhi < klo) return TILE_SKIP;
+  if (qlo >= khi && !ragged) return TILE_FULL;
+  return TILE_PARTIAL;
+}
+
 // Per-element mask of one 32x32 accumulator tile whose 16 registers of a lane run over rows
 // row0 + 8*(v/4) + (v%4)  (row0 already includes the lane's 4*h) of the OTHER side than the lane's
 // own row: KEYS_IN_REGS = true, registers are key rows and the lane owns a query (position
@@ -287,11 +299,15 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& x, int c) {
 
 // Work-group index -> (kv key = batch*Hkv + kv head, head within group, q tile), such that all work
 // on one (batch, kv head) lands on one XCD (work-groups are dealt round-robin to the 8 XCDs, each
-// with its own L2) and heavier tiles (higher rows) start first.
+// with its own L2) and heavier tiles start first.  Under a causal mask a query tile is heavier the
+// higher its rows (HIGH_FIRST), a key tile the lower its rows.  Heavy-first is also what keeps the
+// work-groups that share an L2 in step: the ones running together then walk the other axis at the
+// same place at the same time, so each tile of it is fetched from HBM once.
 struct BlockMap {
   int key, head_in_group, tile;
   bool valid;
 };
+template <bool HIGH_FIRST>
 __device__ __forceinline__ BlockMap map_block(int n, int n_keys, int group, int tiles) {
   const int xcd = n & 7, slot = n >> 3;
   const int per_key = group * tiles;
@@ -299,7 +315,8 @@ __device__ __forceinline__ BlockMap map_block(int n, int n_keys, int group, int 
   int local_key = slot / per_key, rem = slot - local_key * per_key;
   m.key = local_key * 8 + xcd;
   m.head_in_group = rem / tiles;
-  m.tile = tiles - 1 - (rem - m.head_in_group * tiles);
+  const int t = rem - m.head_in_group * tiles;
+  m.tile = HIGH_FIRST ? tiles - 1 - t : t;
   m.valid = m.key < n_keys;
   return m;
 }
@@ -313,5 +330,56 @@ struct TileRuns {
   __host__ __device__ int total() const { return len[0] + len[1]; }
   __host__ __device__ int tile_of(int i) const { return i < len[0] ? start[0] + i : start[1] + (i - len[0]); }
 };
+
+// Tiles of TILE rows along the query axis (Q_AXIS) or the key axis that can hold a pair visible to
+// the other side, in closed form: under a causal mask the rows of a query segment that see a key
+// range are the suffix with position >= `bound` (the lowest key position), the rows of a key segment
+// seen by a query range the prefix with position <= `bound` (the highest query position); a chunk
+// has at most two segments, hence at most two runs.  A tile in a run may still turn out empty for
+// a narrower row range; a tile outside the runs never holds a visible pair.
+template <bool Q_AXIS, int TILE>
+__host__ __device__ __forceinline__ TileRuns visible_tiles(const MaskDev& mk, int bound, int rows) {
+  TileRuns tr{{0, 0}, {0, 0}};
+  if (rows <= 0) return tr;
+  if (!mk.causal) {
+    tr.len[0] = (rows + TILE - 1) / TILE;
+    return tr;
+  }
+  const int nseg = Q_AXIS ? mk.q_nseg : mk.k_nseg;
+  const int seg_len = nseg > 1 ? (Q_AXIS ? mk.q_seg_len : mk.k_seg_len) : rows;
+  int n = 0, prev_end = 0;
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {   // constant indices only: the mask must stay in registers
+    if (s >= nseg) break;
+    const int pos0 = Q_AXIS ? mk.q_seg_pos[s] : mk.k_seg_pos[s];
+    int r0 = 0, r1 = seg_len;   // visible rows of the segment, counted from its start
+    if (Q_AXIS) {
+      const int need = bound - pos0;
+      r0 = need <= 0 ? 0 : (need + mk.pos_stride - 1) / mk.pos_stride;
+    } else {
+      const int room = bound - pos0;
+      const int cnt = room < 0 ? 0 : room / mk.pos_stride + 1;
+      r1 = cnt < seg_len ? cnt : seg_len;
+    }
+    if (r0 >= r1) continue;
+    int a = (s * seg_len + r0) / TILE;
+    const int b = (s * seg_len + r1 + TILE - 1) / TILE;
+    a = a > prev_end ? a : prev_end;
+    if (a >= b) continue;
+    if (s == 1 && n == 1 && a == prev_end) {
+      tr.len[0] += b - a;
+    } else if (n == 0) {
+      tr.start[0] = a;
+      tr.len[0] = b - a;
+      n = 1;
+    } else {
+      tr.start[1] = a;
+      tr.len[1] = b - a;
+      n = 2;
+    }
+    prev_end = b;
+  }
+  return tr;
+}
 
 }  // namespace burst

@@ -27,7 +27,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
   extern __shared__ __attribute__((aligned(16))) char smem[];  // [2 buffers][K tile, V tile]
 
   const int group = p.q_heads / p.kv_heads;
-  const BlockMap bm = map_block(blockIdx.x, p.batch * p.kv_heads, group, p.q_runs.total());
+  const BlockMap bm = map_block<true>(blockIdx.x, p.batch * p.kv_heads, group, p.q_runs.total());
   if (!bm.valid) return;
   const int b = bm.key / p.kv_heads, hk = bm.key - b * p.kv_heads, hq = hk * group + bm.head_in_group;
 
