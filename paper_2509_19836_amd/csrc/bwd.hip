@@ -149,21 +149,36 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_bwd_dq_kernel(B
 // ---------------------------------------------------------------------------------------------
 // Eight waves per work-group, two per SIMD, in two roles that share each block of 32 key rows:
 //   P-wave  (waves 0-3): K rows in registers; S = Q K^T, P = exp2(..) -> bf16, hands P over through
-//                        LDS, then dV^T += dO^T P.
+//                        LDS, then dV^T += dO^T P.  Also stages the next query tile.
 //   dS-wave (waves 4-7): V rows in registers; dP = dO V^T, then dS = P o (dP - D), dK^T += Q^T dS.
 // Each role carries one 32 x D accumulator and one stationary operand, which is what lets two
-// waves fit on a SIMD; the exp-heavy role and the light one overlap on the same SIMD.
-// Two barriers per query tile: [S, P | dP]  barrier  [dV | dS, dK; stage next tile]  barrier.
+// waves fit on a SIMD.  The dS-wave finishes a query tile one iteration late: in iteration t it
+// first turns the dP it kept in registers and the P of tile t-1 into dS and dK, and only then
+// computes dP of tile t, while the P-wave of the same SIMD runs S, softmax, dV of tile t and moves
+// tile t+1 from global memory to LDS.  One barrier per tile: everything a wave reads in iteration
+// t was written before the barrier that ended iteration t-1.
+//   LDS: Q tiles and D rows in three slots (tile t-1 for dK, t for S, t+1 being staged), dO tiles,
+//   lse rows and the P hand-over area in two.
+template <int D, int BQ>
+struct DkdvLds {
+  static constexpr int PITCH = 2 * D + 16, TILE = BQ * PITCH, QBK = BQ / 32;
+  static constexpr int Q_OFF = 0, DO_OFF = 3 * TILE, LSE_OFF = 5 * TILE, D_OFF = LSE_OFF + 2 * BQ * 4;
+  static constexpr int P_OFF = D_OFF + 3 * BQ * 4;
+  static constexpr int P_SLOT = 4 * QBK * 2 * 64;          // bf16x8 units: [pair][qb][half][lane]
+  static constexpr int BYTES = P_OFF + 2 * P_SLOT * 16;
+};
+
 template <int D, int BQ, int ROLE>
 __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b, int hk, int kv_tile, int pair) {
-  constexpr int DK = D / 16, DB = D / 32, QBK = BQ / 32, BKV = 128, NT = 512;
-  constexpr int PITCH = 2 * D + 16;
-  constexpr int TILE = BQ * PITCH;
-  constexpr int BUF = 2 * TILE + 2 * BQ * 4;   // Q tile, dO tile, lse2[BQ], D[BQ]
-  bf16x8* pbuf = reinterpret_cast<bf16x8*>(smem + 2 * BUF);     // [pair][qb][half][lane]
+  constexpr int DK = D / 16, DB = D / 32, QBK = BQ / 32, BKV = 128, NT = 256;   // NT: staging threads
+  using L = DkdvLds<D, BQ>;
+  constexpr int PITCH = L::PITCH, TILE = L::TILE;
+  float* lse_slots = reinterpret_cast<float*>(smem + L::LSE_OFF);
+  float* d_slots = reinterpret_cast<float*>(smem + L::D_OFF);
+  bf16x8* pbuf = reinterpret_cast<bf16x8*>(smem + L::P_OFF);
 
   const int group = p.q_heads / p.kv_heads;
-  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, h = lane >> 5;
+  const int tid = threadIdx.x & 255, lane = tid & 63, r = lane & 31, h = lane >> 5;   // tid within the role
   const int sq = p.sq, sk = p.sk;
   const MaskDev mk = p.mask;
   const int k_blk0 = p.k_runs.tile_of(kv_tile) * BKV, k_blk1 = min(k_blk0 + BKV, sk);
@@ -190,69 +205,109 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
   range_minmax(k_blk0, k_blk1, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride, klo_blk, khi_blk);
   const bool has_keys = k_w0 < k_w1;
   if (has_keys) range_minmax(k_w0, k_w1, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride, klo_w, khi_w);
+  // Class of a whole query tile against this pair's 32 key rows (same for both waves of the pair).
+  // A tile the mask only partly empties is computed whole with the per-element predicate.
+  auto tile_class = [&](int q0) {
+    if (!has_keys) return (int)TILE_SKIP;
+    int qlo, qhi;
+    range_minmax(q0, min(q0 + BQ, sq), mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, qlo, qhi);
+    return classify_range<true>(mk, qlo, qhi, klo_w, khi_w, q0 + BQ > sq);
+  };
 
   // Walk over (query head of the group, query tile that can see the key block), flattened so the
-  // double buffering runs across head boundaries.  Only counters and compares per step: the per-head
-  // base pointers change on a head switch, the tile index comes from the precomputed runs.
+  // pipeline runs across head boundaries.  The visible tiles of a head are one or two runs of
+  // consecutive tiles; inside a run the cursor moves by adding constants, and only a run or head
+  // change recomputes addresses.
   const TileRuns qr = visible_tiles<true, BQ>(mk, klo_blk, sq);
-  const int per_head = qr.total();
-  const int n_items = group * per_head;
+  const int n_items = group * qr.total();
+  int c_run = 0, c_left = qr.len[0], c_head = 0;   // cursor: run, tiles left in it, head of the group
+  int q0n = qr.start[0] * BQ;                      // first row of the tile under the cursor
 
-  TileStager<D, BQ, NT> stage_q, stage_do;
-  stage_q.init(p.q.ss, tid);
-  stage_do.init(p.d_o.ss, tid);
-  float stage_row = 0.f;   // threads [0, BQ): lse2 of a row; threads [BQ, 2*BQ): D of a row
-  const __bf16 *q_head, *do_head;
-  const float* row_head;   // lse (threads < BQ) or D of the head being staged
-  auto set_head = [&](int g) {
-    const int hq = hk * group + g;
-    q_head = (const __bf16*)p.q.ptr + b * p.q.sb + hq * p.q.sh;
-    do_head = (const __bf16*)p.d_o.ptr + b * p.d_o.sb + hq * p.d_o.sh;
+  TileStager<D, BQ, NT> stage_q, stage_do;         // P-wave only
+  float stage_row = 0.f;   // threads [0, BQ): lse of a row; threads [BQ, 2*BQ): D of a row
+  const char *q_tile = nullptr, *do_tile = nullptr;   // first row of the tile under the cursor
+  const float* row_head = nullptr;                    // lse (threads < BQ) or D of the cursor's head
+  const int64_t q_step = (int64_t)BQ * p.q.ss * 2, do_step = (int64_t)BQ * p.d_o.ss * 2;
+  if (ROLE == 0) {
+    stage_q.init(p.q.ss, tid);
+    stage_do.init(p.d_o.ss, tid);
+  }
+  auto point = [&]() {   // addresses of the tile under the cursor, from scratch
+    if (ROLE != 0) return;
+    const int hq = hk * group + c_head;
+    q_tile = reinterpret_cast<const char*>((const __bf16*)p.q.ptr + b * p.q.sb + hq * p.q.sh + (int64_t)q0n * p.q.ss);
+    do_tile = reinterpret_cast<const char*>((const __bf16*)p.d_o.ptr + b * p.d_o.sb + hq * p.d_o.sh +
+                                            (int64_t)q0n * p.d_o.ss);
     row_head = tid < BQ ? p.lse.ptr + b * p.lse.sb + hq * p.lse.sh : p.d.ptr + b * p.d.sb + hq * p.d.sh;
   };
-  auto issue = [&](int q0) {
-    stage_q.load(q_head, p.q.ss, q0, sq, tid);
-    stage_do.load(do_head, p.d_o.ss, q0, sq, tid);
-    // raw value only: converting here would wait for this load, and with it for the tile loads
-    if (tid < 2 * BQ) stage_row = row_head[min(q0 + (tid & (BQ - 1)), sq - 1)];
+  auto advance = [&]() {   // cursor to the next item
+    if (--c_left > 0) {
+      q0n += BQ;
+      q_tile += q_step;
+      do_tile += do_step;
+    } else {
+      if (c_run == 0 && qr.len[1] > 0) {
+        c_run = 1;
+      } else {
+        c_run = 0;
+        ++c_head;
+      }
+      c_left = c_run ? qr.len[1] : qr.len[0];
+      q0n = (c_run ? qr.start[1] : qr.start[0]) * BQ;
+      if (c_head < group) point();
+    }
   };
-  auto commit = [&](char* dst) {
-    stage_q.store(dst);
-    stage_do.store(dst + TILE);
-    if (tid < 2 * BQ) reinterpret_cast<float*>(dst + 2 * TILE)[tid] = tid < BQ ? lse_to_log2(stage_row) : stage_row;
+  auto issue = [&]() {   // loads of the tile under the cursor
+    if (ROLE != 0) return;
+    if (q0n + BQ <= sq) {
+      stage_q.load_at(q_tile);
+      stage_do.load_at(do_tile);
+    } else {   // last tile of a ragged chunk: row indices clamped per thread
+      stage_q.load(reinterpret_cast<const __bf16*>(q_tile) - (int64_t)q0n * p.q.ss, p.q.ss, q0n, sq, tid);
+      stage_do.load(reinterpret_cast<const __bf16*>(do_tile) - (int64_t)q0n * p.d_o.ss, p.d_o.ss, q0n, sq, tid);
+    }
+    // raw value only: converting here would wait for this load, and with it for the tile loads
+    if (tid < 2 * BQ) stage_row = row_head[min(q0n + (tid & (BQ - 1)), sq - 1)];
+  };
+  auto commit = [&](int q_slot, int par) {   // q_slot: Q / D slot, par: dO / lse slot
+    if (ROLE != 0) return;
+    stage_q.store(smem + L::Q_OFF + q_slot * TILE);
+    stage_do.store(smem + L::DO_OFF + par * TILE);
+    if (tid < BQ) lse_slots[par * BQ + tid] = lse_to_log2(stage_row);
+    else if (tid < 2 * BQ) d_slots[q_slot * BQ + tid - BQ] = stage_row;
   };
 
   wait_global_loads();
-  int idx = 0, head = 0;    // position of the NEXT item to stage: run index within the head, head of the group
-  set_head(0);
+  int q0 = 0, cls = TILE_SKIP;   // first row and class of the tile in slot (qs_cur, par)
   if (n_items > 0) {
-    issue(qr.tile_of(0) * BQ);
-    commit(smem);
+    point();
+    issue();
+    commit(0, 0);
+    q0 = q0n;
+    cls = tile_class(q0n);
+    advance();
   }
   __syncthreads();
-  int buf = 0;
-  for (int it = 0; it < n_items; ++it) {
-    const int q0 = qr.tile_of(idx) * BQ;   // tile in LDS now
-    if (++idx == per_head) {
-      idx = 0;
-      if (++head < group) set_head(head);
-    }
+  int qs_prev = 2, qs_cur = 0, qs_next = 1, par = 0;
+  int cls_prev = TILE_SKIP;
+  f32x16 dp[QBK];   // dS-wave: dP of the tile staged one iteration ago
+  // n_items + 1 iterations: the last one only drains the dS-wave's lagging half
+  for (int it = 0; it <= n_items; ++it) {
     const bool more = it + 1 < n_items;
-    if (more) issue(qr.tile_of(idx) * BQ);
-    const char* qt_ = smem + buf * BUF;
-    const char* dot_ = qt_ + TILE;
-    const float* rowv = reinterpret_cast<const float*>(qt_ + 2 * TILE);
-    // Class of the whole query tile against this pair's 32 key rows (same for both waves of the
-    // pair).  A tile the mask only partly empties is computed whole with the per-element predicate.
-    int cls = TILE_SKIP;
-    if (has_keys) {
-      int qlo, qhi;
-      range_minmax(q0, min(q0 + BQ, sq), mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, qlo, qhi);
-      cls = classify_range<true>(mk, qlo, qhi, klo_w, khi_w, q0 + BQ > sq);
+    int q0_next = 0, cls_next = TILE_SKIP;
+    if (more) {
+      issue();
+      q0_next = q0n;
+      cls_next = tile_class(q0n);
+      advance();
     }
+    const char* dot_ = smem + L::DO_OFF + par * TILE;
     if (ROLE == 0) {
-      bf16x8 pk[2 * QBK];
       if (cls != TILE_SKIP) {
+        const char* qt_ = smem + L::Q_OFF + qs_cur * TILE;
+        const float* lse2 = lse_slots + par * BQ;
+        bf16x8* pw = pbuf + par * L::P_SLOT;
+        bf16x8 pk[2 * QBK];
         f32x16 s[QBK];
 #pragma unroll
         for (int qb = 0; qb < QBK; ++qb) zero16(s[qb]);
@@ -262,39 +317,34 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
           if (cls == TILE_PARTIAL) mask_tile<false>(s[qb], mk, q0 + qb * 32 + 4 * h, sq, kpos);
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
-            const f32x4 l4 = *reinterpret_cast<const f32x4*>(rowv + qb * 32 + 8 * g + 4 * h);
+            const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse2 + qb * 32 + 8 * g + 4 * h);
 #pragma unroll
             for (int j = 0; j < 4; ++j) s[qb][4 * g + j] = __builtin_amdgcn_exp2f(c * s[qb][4 * g + j] - l4[j]);
           }
           pk[2 * qb] = pack8(s[qb], 0);
           pk[2 * qb + 1] = pack8(s[qb], 1);
-          pbuf[((pair * QBK + qb) * 2 + 0) * 64 + lane] = pk[2 * qb];
-          pbuf[((pair * QBK + qb) * 2 + 1) * 64 + lane] = pk[2 * qb + 1];
+          pw[((pair * QBK + qb) * 2 + 0) * 64 + lane] = pk[2 * qb];
+          pw[((pair * QBK + qb) * 2 + 1) * 64 + lane] = pk[2 * qb + 1];
         }
+        gemm_cols<PITCH, DB, 2 * QBK, kColsAhead>(dot_, 0, pk, acc, lane);
       }
-      __syncthreads();
-      if (cls != TILE_SKIP) gemm_cols<PITCH, DB, 2 * QBK, kColsAhead>(dot_, 0, pk, acc, lane);
     } else {
-      f32x16 dp[QBK];
-      if (cls != TILE_SKIP) {
-#pragma unroll
-        for (int qb = 0; qb < QBK; ++qb) zero16(dp[qb]);
-        gemm_rows<PITCH, QBK, DK, kRowsAhead>(dot_, 0, xreg, dp, r, h);
-      }
-      __syncthreads();
-      if (cls != TILE_SKIP) {
+      if (cls_prev != TILE_SKIP) {
+        const char* qt_ = smem + L::Q_OFF + qs_prev * TILE;
+        const float* dv_ = d_slots + qs_prev * BQ;
+        const bf16x8* pr_ = pbuf + (par ^ 1) * L::P_SLOT;
         bf16x8 dsp[2 * QBK];
 #pragma unroll
         for (int qb = 0; qb < QBK; ++qb) {
-          const bf16x8 q0_ = pbuf[((pair * QBK + qb) * 2 + 0) * 64 + lane];
-          const bf16x8 q1_ = pbuf[((pair * QBK + qb) * 2 + 1) * 64 + lane];
+          const bf16x8 p0 = pr_[((pair * QBK + qb) * 2 + 0) * 64 + lane];
+          const bf16x8 p1 = pr_[((pair * QBK + qb) * 2 + 1) * 64 + lane];
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
-            const f32x4 d4 = *reinterpret_cast<const f32x4*>(rowv + BQ + qb * 32 + 8 * g + 4 * h);
+            const f32x4 d4 = *reinterpret_cast<const f32x4*>(dv_ + qb * 32 + 8 * g + 4 * h);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
               const int v = 4 * g + j;
-              const float pr = (float)(v < 8 ? q0_[v & 7] : q1_[v & 7]);
+              const float pr = (float)(v < 8 ? p0[v & 7] : p1[v & 7]);
               dp[qb][v] = pr * (dp[qb][v] - d4[j]);
             }
           }
@@ -303,10 +353,22 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
         }
         gemm_cols<PITCH, DB, 2 * QBK, kColsAhead>(qt_, 0, dsp, acc, lane);
       }
+      if (cls != TILE_SKIP) {
+#pragma unroll
+        for (int qb = 0; qb < QBK; ++qb) zero16(dp[qb]);
+        gemm_rows<PITCH, QBK, DK, kRowsAhead>(dot_, 0, xreg, dp, r, h);
+      }
     }
-    if (more) commit(smem + (buf ^ 1) * BUF);
+    if (more) commit(qs_next, par ^ 1);
     __syncthreads();
-    buf ^= 1;
+    const int t_ = qs_prev;
+    qs_prev = qs_cur;
+    qs_cur = qs_next;
+    qs_next = t_;
+    par ^= 1;
+    cls_prev = cls;
+    q0 = q0_next;
+    cls = cls_next;
   }
 
   if (k_w0 + r < sk) {
@@ -328,7 +390,7 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
 
 template <int D, int BQ>
 __global__ __launch_bounds__(512, 1) void step_bwd_dkdv_kernel(BwdParams p) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];   // [2][tile buffers], then the P hand-over area
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // laid out by DkdvLds
   const BlockMap bm = map_block<false>(blockIdx.x, p.batch * p.kv_heads, 1, p.k_runs.total());
   if (!bm.valid) return;
   const int b = bm.key / p.kv_heads, hk = bm.key - b * p.kv_heads;
@@ -361,7 +423,7 @@ static hipError_t launch_bwd_t(BwdParams p, hipStream_t stream) {
   }
   if (p.dk.ptr) {
     constexpr int BQ = 64;
-    constexpr int LDS = 2 * (2 * BQ * (2 * D + 16) + 2 * BQ * 4) + 4 * (BQ / 32) * 2 * 64 * 16;
+    constexpr int LDS = DkdvLds<D, BQ>::BYTES;
     p.k_runs = nonempty_runs(p.mask, p.sq, p.sk, 128, false);
     if (p.k_runs.total() < (p.sk + 127) / 128) {
       if (!p.acc_dk) e = launch_zero_tensor(p.dk, p.batch, p.sk, p.kv_heads, p.head_dim, stream);

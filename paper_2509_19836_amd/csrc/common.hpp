@@ -19,6 +19,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#ifndef BURST_MFMA_PRIO
+#define BURST_MFMA_PRIO 2
+#endif
+
 namespace burst {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -184,11 +188,21 @@ struct TileStager {
   u32x4 regs[PASSES];
   uint32_t lane_off;    // (tid / CPR) * ss + (tid % CPR) * 8, elements
   uint32_t lds_off[PASSES];
+  uint32_t src_off[PASSES];   // byte offset of this thread's chunk of pass i from the tile's first row
 
   __device__ __forceinline__ void init(int64_t ss, int tid) {
     lane_off = (uint32_t)(tid / CPR) * (uint32_t)ss + (uint32_t)(tid % CPR) * 8u;
 #pragma unroll
-    for (int i = 0; i < PASSES; ++i) lds_off[i] = lds_row(tid / CPR + i * RPP) * PITCH + (tid % CPR) * 16;
+    for (int i = 0; i < PASSES; ++i) {
+      lds_off[i] = lds_row(tid / CPR + i * RPP) * PITCH + (tid % CPR) * 16;
+      src_off[i] = 2u * ((uint32_t)(tid / CPR + i * RPP) * (uint32_t)ss + (uint32_t)(tid % CPR) * 8u);
+    }
+  }
+  // A tile that lies wholly inside the tensor, given the (wave-uniform) address of its first row:
+  // uniform base plus a precomputed 32-bit lane offset, no address arithmetic per load.
+  __device__ __forceinline__ void load_at(const char* tile) {
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i) regs[i] = *reinterpret_cast<const u32x4*>(tile + src_off[i]);
   }
   // base: first row of the tensor slice; row0: first tile row; nrows: rows in the slice (> row0)
   __device__ __forceinline__ void load(const __bf16* base, int64_t ss, int row0, int nrows, int tid) {
@@ -212,6 +226,15 @@ struct TileStager {
   }
 };
 
+// Scope of a stream of MFMAs: the wave runs at raised issue priority.  A SIMD issues one vector-class
+// instruction at a time and picks the oldest ready wave; without this, a co-resident wave in a
+// dense vector phase (softmax, dS) keeps winning the issue slot and the matrix pipe idles, although
+// an MFMA needs only one slot in eight.
+struct MatrixPhase {
+  __device__ __forceinline__ MatrixPhase() { __builtin_amdgcn_s_setprio(BURST_MFMA_PRIO); }
+  __device__ __forceinline__ ~MatrixPhase() { __builtin_amdgcn_s_setprio(0); }
+};
+
 struct NoHook {
   __device__ __forceinline__ void operator()(int) const {}
 };
@@ -228,6 +251,7 @@ __device__ __forceinline__ void gemm_rows(const char* tile, int row0, const bf16
                                           int r, int h, Hook&& hook = Hook()) {
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   bf16x8 a[DK][NB];
+  MatrixPhase prio;
 #pragma unroll
   for (int ks = 0; ks < PRE && ks < DK; ++ks)
 #pragma unroll
@@ -252,6 +276,7 @@ template <int PITCH, int DK, int PRE>
 __device__ __forceinline__ void gemm_rows_pair(const char* tile0, const char* tile1, int row0, const bf16x8 (&b0)[DK],
                                                const bf16x8 (&b1)[DK], f32x16& acc0, f32x16& acc1, int r, int h) {
   bf16x8 a0[DK], a1[DK];
+  MatrixPhase prio;
 #pragma unroll
   for (int ks = 0; ks < PRE && ks < DK; ++ks) {
     a0[ks] = lds_rows_operand<PITCH>(tile0, row0, ks * 16, r, h);
@@ -278,6 +303,7 @@ __device__ __forceinline__ void gemm_cols(const char* tile, int row0, const bf16
   // operands in use order: i = c * DB + db; fetched AHEAD operands before use
   constexpr int N = NC * DB, AHEAD = PRE;   // PRE counts operands here
   bf16x8 a[N];
+  MatrixPhase prio;
 #pragma unroll
   for (int i = 0; i < AHEAD && i < N; ++i) a[i] = lds_cols_operand<PITCH>(tile, row0 + 16 * (i / DB), (i % DB) * 32, lane);
 #pragma unroll
