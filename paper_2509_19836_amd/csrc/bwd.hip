@@ -21,6 +21,9 @@
 
 namespace burst {
 
+#ifndef BURST_DQ_KB
+#define BURST_DQ_KB 2   // 32-row key blocks per LDS tile of the dQ kernel
+#endif
 #ifndef BURST_DQ_BQ
 #define BURST_DQ_BQ 256
 #endif
@@ -207,12 +210,9 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
   if (has_keys) range_minmax(k_w0, k_w1, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride, klo_w, khi_w);
   // Class of a whole query tile against this pair's 32 key rows (same for both waves of the pair).
   // A tile the mask only partly empties is computed whole with the per-element predicate.
-  auto tile_class = [&](int q0) {
-    if (!has_keys) return (int)TILE_SKIP;
-    int qlo, qhi;
-    range_minmax(q0, min(q0 + BQ, sq), mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, qlo, qhi);
-    return classify_range<true>(mk, qlo, qhi, klo_w, khi_w, q0 + BQ > sq);
-  };
+  BlockClassifier<true> q_class;
+  q_class.init(mk, klo_w, khi_w, sq, !has_keys);
+  auto tile_class = [&](int q0) { return q_class(mk, q0, min(q0 + BQ, sq), q0 + BQ > sq); };
 
   // Walk over (query head of the group, query tile that can see the key block), flattened so the
   // pipeline runs across head boundaries.  The visible tiles of a head are one or two runs of
@@ -406,7 +406,7 @@ static hipError_t launch_bwd_t(BwdParams p, hipStream_t stream) {
   const int n_keys = p.batch * p.kv_heads, group = p.q_heads / p.kv_heads;
   hipError_t e = hipSuccess;
   if (p.dq.ptr) {
-    constexpr int KB = 2;
+    constexpr int KB = BURST_DQ_KB;
     constexpr int LDS = 2 * 2 * 32 * KB * (2 * D + 16);
     p.q_runs = nonempty_runs(p.mask, p.sq, p.sk, kDqBQ, true);
     // query tiles that see no key get no work-group: "=" must still leave zeros there

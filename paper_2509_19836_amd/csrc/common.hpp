@@ -105,6 +105,68 @@ __host__ __device__ __forceinline__ int classify_range(const MaskDev& mk, int lo
   return TILE_PARTIAL;
 }
 
+// The same decisions as classify() for many row blocks of one axis against ONE fixed position range
+// [olo, ohi] of the other axis, from per-segment row thresholds computed once: inside a segment
+// positions grow with the row, so on the query axis the rows that see some / all of the keys are a
+// suffix of the segment, on the key axis the rows seen by some / all of the queries a prefix.  A
+// block that straddles the two segments falls back to classify().
+template <bool Q_AXIS>
+struct BlockClassifier {
+  // Q_AXIS: first row that sees some / all keys; else: end of the rows seen by some / all queries;
+  // one pair per segment (scalar members: the thresholds must stay in registers)
+  int32_t some0, some1, all0, all1;
+  int32_t olo, ohi, seg_len, two, empty;
+
+  __host__ __device__ __forceinline__ void init(const MaskDev& mk, int olo_, int ohi_, int rows, bool other_empty) {
+    olo = olo_;
+    ohi = ohi_;
+    empty = other_empty;
+    two = (Q_AXIS ? mk.q_nseg : mk.k_nseg) > 1;
+    seg_len = two ? (Q_AXIS ? mk.q_seg_len : mk.k_seg_len) : rows;
+    segment(mk, 0, Q_AXIS ? mk.q_seg_pos[0] : mk.k_seg_pos[0], some0, all0);
+    segment(mk, seg_len, Q_AXIS ? mk.q_seg_pos[1] : mk.k_seg_pos[1], some1, all1);
+  }
+  __host__ __device__ __forceinline__ void segment(const MaskDev& mk, int start, int pos0, int32_t& some, int32_t& all) const {
+    if (empty) {   // nothing on the other side: every block is empty
+      some = all = Q_AXIS ? 0x7fffffff : -1;
+    } else if (!mk.causal) {
+      some = all = Q_AXIS ? start : start + seg_len;
+    } else if (Q_AXIS) {   // row r of the segment sees key position k iff pos0 + r*stride >= k
+      some = start + rows_below(olo - pos0, mk.pos_stride);
+      all = start + rows_below(ohi - pos0, mk.pos_stride);
+    } else {               // key row r is seen from query position q iff pos0 + r*stride <= q
+      some = start + rows_upto(ohi - pos0, mk.pos_stride);
+      all = start + rows_upto(olo - pos0, mk.pos_stride);
+    }
+  }
+  // rows r >= 0 of a segment with r*stride < gap, capped at the segment length
+  __host__ __device__ __forceinline__ int rows_below(int gap, int stride) const {
+    const int n = gap <= 0 ? 0 : (gap + stride - 1) / stride;
+    return n < seg_len ? n : seg_len;
+  }
+  // rows r >= 0 of a segment with r*stride <= room, capped at the segment length
+  __host__ __device__ __forceinline__ int rows_upto(int room, int stride) const {
+    const int n = room < 0 ? 0 : room / stride + 1;
+    return n < seg_len ? n : seg_len;
+  }
+  // block of rows [r0, r1), r1 > r0, both inside the chunk
+  __host__ __device__ __forceinline__ int operator()(const MaskDev& mk, int r0, int r1, bool ragged) const {
+    if (two && r0 < seg_len && r1 > seg_len) return classify_straddle(mk, r0, r1, ragged);
+    const bool second = two && r0 >= seg_len;
+    const int some_s = second ? some1 : some0, all_s = second ? all1 : all0;
+    const bool skip = Q_AXIS ? r1 <= some_s : r0 >= some_s;
+    const bool full = (Q_AXIS ? r0 >= all_s : r1 <= all_s) && !ragged;
+    return skip ? TILE_SKIP : (full ? TILE_FULL : TILE_PARTIAL);
+  }
+  __host__ __device__ __forceinline__ int classify_straddle(const MaskDev& mk, int r0, int r1, bool ragged) const {
+    if (empty) return TILE_SKIP;
+    const int p0 = Q_AXIS ? mk.q_seg_pos[0] : mk.k_seg_pos[0], p1 = Q_AXIS ? mk.q_seg_pos[1] : mk.k_seg_pos[1];
+    const int lo0 = p0 + r0 * mk.pos_stride, hi0 = p0 + (seg_len - 1) * mk.pos_stride;
+    const int lo1 = p1, hi1 = p1 + (r1 - 1 - seg_len) * mk.pos_stride;
+    return classify_range<Q_AXIS>(mk, lo0 < lo1 ? lo0 : lo1, hi0 > hi1 ? hi0 : hi1, olo, ohi, ragged);
+  }
+};
+
 // Per-element mask of one 32x32 accumulator tile whose 16 registers of a lane run over rows
 // row0 + 8*(v/4) + (v%4)  (row0 already includes the lane's 4*h) of the OTHER side than the lane's
 // own row: KEYS_IN_REGS = true, registers are key rows and the lane owns a query (position
