@@ -235,6 +235,66 @@ __device__ __forceinline__ float half_swap(float x) {
   return __shfl_xor(x, 32, 64);
 }
 
+// The tiles of an axis that have any visible pair, as up to two runs of consecutive tile indices
+// (a causal mask over one- or two-segment chunks never needs more).  Only these are launched: an
+// empty work-group costs a dispatch slot, and many of them in a row starve the other CUs.
+struct TileRuns {
+  int32_t start[2], len[2];
+  __host__ __device__ int total() const { return len[0] + len[1]; }
+  __host__ __device__ int tile_of(int i) const { return i < len[0] ? start[0] + i : start[1] + (i - len[0]); }
+};
+
+// Tiles of TILE rows along the query axis (Q_AXIS) or the key axis that can hold a pair visible to
+// the other side, in closed form: under a causal mask the rows of a query segment that see a key
+// range are the suffix with position >= `bound` (the lowest key position), the rows of a key segment
+// seen by a query range the prefix with position <= `bound` (the highest query position); a chunk
+// has at most two segments, hence at most two runs.  A tile in a run may still turn out empty for
+// a narrower row range; a tile outside the runs never holds a visible pair.
+template <bool Q_AXIS, int TILE>
+__host__ __device__ __forceinline__ TileRuns visible_tiles(const MaskDev& mk, int bound, int rows) {
+  TileRuns tr{{0, 0}, {0, 0}};
+  if (rows <= 0) return tr;
+  if (!mk.causal) {
+    tr.len[0] = (rows + TILE - 1) / TILE;
+    return tr;
+  }
+  const int nseg = Q_AXIS ? mk.q_nseg : mk.k_nseg;
+  const int seg_len = nseg > 1 ? (Q_AXIS ? mk.q_seg_len : mk.k_seg_len) : rows;
+  int n = 0, prev_end = 0;
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {   // constant indices only: the mask must stay in registers
+    if (s >= nseg) break;
+    const int pos0 = Q_AXIS ? mk.q_seg_pos[s] : mk.k_seg_pos[s];
+    int r0 = 0, r1 = seg_len;   // visible rows of the segment, counted from its start
+    if (Q_AXIS) {
+      const int need = bound - pos0;
+      r0 = need <= 0 ? 0 : (need + mk.pos_stride - 1) / mk.pos_stride;
+    } else {
+      const int room = bound - pos0;
+      const int cnt = room < 0 ? 0 : room / mk.pos_stride + 1;
+      r1 = cnt < seg_len ? cnt : seg_len;
+    }
+    if (r0 >= r1) continue;
+    int a = (s * seg_len + r0) / TILE;
+    const int b = (s * seg_len + r1 + TILE - 1) / TILE;
+    a = a > prev_end ? a : prev_end;
+    if (a >= b) continue;
+    if (s == 1 && n == 1 && a == prev_end) {
+      tr.len[0] += b - a;
+    } else if (n == 0) {
+      tr.start[0] = a;
+      tr.len[0] = b - a;
+      n = 1;
+    } else {
+      tr.start[1] = a;
+      tr.len[1] = b - a;
+      n = 2;
+    }
+    prev_end = b;
+  }
+  return tr;
+}
+
 // Stage a [ROWS x D] bf16 tile: global (row-major, row stride `ss` elements) -> registers -> LDS,
 // by THREADS threads.  Split in two so the loads can be issued before the compute they overlap
 // with.  The per-lane part of the address is one 32-bit element offset computed once; the
@@ -285,6 +345,66 @@ struct TileStager {
   __device__ __forceinline__ void store(char* tile) const {
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) *reinterpret_cast<u32x4*>(tile + lds_off[i]) = regs[i];
+  }
+};
+
+// Walk of a query block over the key tiles (BK rows of K and of V) it can see, with the staging
+// of the tiles.  The visible tiles form at most two runs of consecutive tiles; inside a run the
+// next tile is the next BK rows, so the cursor and the two tile addresses move by adding constants
+// and a load needs no address arithmetic; only the jump to the second run multiplies.
+template <int D, int BK, int NT>
+struct KvWalk {
+  TileStager<D, BK, NT> stage_k, stage_v;
+  TileRuns runs;
+  int n_tiles;            // tiles the walk visits
+  int run, left, k0;      // cursor: run, tiles left in it, first key row of its tile
+  int sk;
+  const char *k_base, *v_base, *k_tile, *v_tile;   // row 0 of the head; first row of the cursor's tile
+  int64_t k_row, v_row;   // bytes per key row
+
+  // q_hi: highest position among the query rows of the work-group
+  __device__ __forceinline__ void init(const MaskDev& mk, const TensorDev& k, const TensorDev& v, int b, int hk, int sk_,
+                                       int q_hi, int tid) {
+    sk = sk_;
+    runs = visible_tiles<false, BK>(mk, q_hi, sk);
+    n_tiles = runs.total();
+    run = 0;
+    left = runs.len[0];
+    k0 = runs.start[0] * BK;
+    k_row = k.ss * 2;
+    v_row = v.ss * 2;
+    k_base = reinterpret_cast<const char*>((const __bf16*)k.ptr + b * k.sb + hk * k.sh);
+    v_base = reinterpret_cast<const char*>((const __bf16*)v.ptr + b * v.sb + hk * v.sh);
+    k_tile = k_base + k0 * k_row;
+    v_tile = v_base + k0 * v_row;
+    stage_k.init(k.ss, tid);
+    stage_v.init(v.ss, tid);
+  }
+  __device__ __forceinline__ void issue(int tid) {   // loads of the cursor's tile
+    if (k0 + BK <= sk) {
+      stage_k.load_at(k_tile);
+      stage_v.load_at(v_tile);
+    } else {   // last tile of a ragged chunk: row indices clamped per thread
+      stage_k.load(reinterpret_cast<const __bf16*>(k_base), k_row >> 1, k0, sk, tid);
+      stage_v.load(reinterpret_cast<const __bf16*>(v_base), v_row >> 1, k0, sk, tid);
+    }
+  }
+  __device__ __forceinline__ void advance() {
+    if (--left > 0) {
+      k0 += BK;
+      k_tile += BK * k_row;
+      v_tile += BK * v_row;
+    } else {
+      run = 1;
+      left = runs.len[1];
+      k0 = runs.start[1] * BK;
+      k_tile = k_base + k0 * k_row;
+      v_tile = v_base + k0 * v_row;
+    }
+  }
+  __device__ __forceinline__ void commit(char* k_lds, char* v_lds) const {
+    stage_k.store(k_lds);
+    stage_v.store(v_lds);
   }
 };
 
@@ -409,65 +529,5 @@ __device__ __forceinline__ BlockMap map_block(int n, int n_keys, int group, int 
   return m;
 }
 inline int mapped_grid(int n_keys, int group, int tiles) { return 8 * ((n_keys + 7) / 8) * group * tiles; }
-
-// The tiles of an axis that have any visible pair, as up to two runs of consecutive tile indices
-// (a causal mask over one- or two-segment chunks never needs more).  Only these are launched: an
-// empty work-group costs a dispatch slot, and many of them in a row starve the other CUs.
-struct TileRuns {
-  int32_t start[2], len[2];
-  __host__ __device__ int total() const { return len[0] + len[1]; }
-  __host__ __device__ int tile_of(int i) const { return i < len[0] ? start[0] + i : start[1] + (i - len[0]); }
-};
-
-// Tiles of TILE rows along the query axis (Q_AXIS) or the key axis that can hold a pair visible to
-// the other side, in closed form: under a causal mask the rows of a query segment that see a key
-// range are the suffix with position >= `bound` (the lowest key position), the rows of a key segment
-// seen by a query range the prefix with position <= `bound` (the highest query position); a chunk
-// has at most two segments, hence at most two runs.  A tile in a run may still turn out empty for
-// a narrower row range; a tile outside the runs never holds a visible pair.
-template <bool Q_AXIS, int TILE>
-__host__ __device__ __forceinline__ TileRuns visible_tiles(const MaskDev& mk, int bound, int rows) {
-  TileRuns tr{{0, 0}, {0, 0}};
-  if (rows <= 0) return tr;
-  if (!mk.causal) {
-    tr.len[0] = (rows + TILE - 1) / TILE;
-    return tr;
-  }
-  const int nseg = Q_AXIS ? mk.q_nseg : mk.k_nseg;
-  const int seg_len = nseg > 1 ? (Q_AXIS ? mk.q_seg_len : mk.k_seg_len) : rows;
-  int n = 0, prev_end = 0;
-#pragma unroll
-  for (int s = 0; s < 2; ++s) {   // constant indices only: the mask must stay in registers
-    if (s >= nseg) break;
-    const int pos0 = Q_AXIS ? mk.q_seg_pos[s] : mk.k_seg_pos[s];
-    int r0 = 0, r1 = seg_len;   // visible rows of the segment, counted from its start
-    if (Q_AXIS) {
-      const int need = bound - pos0;
-      r0 = need <= 0 ? 0 : (need + mk.pos_stride - 1) / mk.pos_stride;
-    } else {
-      const int room = bound - pos0;
-      const int cnt = room < 0 ? 0 : room / mk.pos_stride + 1;
-      r1 = cnt < seg_len ? cnt : seg_len;
-    }
-    if (r0 >= r1) continue;
-    int a = (s * seg_len + r0) / TILE;
-    const int b = (s * seg_len + r1 + TILE - 1) / TILE;
-    a = a > prev_end ? a : prev_end;
-    if (a >= b) continue;
-    if (s == 1 && n == 1 && a == prev_end) {
-      tr.len[0] += b - a;
-    } else if (n == 0) {
-      tr.start[0] = a;
-      tr.len[0] = b - a;
-      n = 1;
-    } else {
-      tr.start[1] = a;
-      tr.len[1] = b - a;
-      n = 2;
-    }
-    prev_end = b;
-  }
-  return tr;
-}
 
 }  // namespace burst

@@ -39,9 +39,6 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
   const int q_w0 = q_blk0 + wave * 32;                   // first row of the wave
   const int q_w1 = min(q_w0 + 32, sq);                   // may be <= q_w0: the wave only helps staging
 
-  const __bf16* kg = (const __bf16*)p.k.ptr + b * p.k.sb + hk * p.k.sh;
-  const __bf16* vg = (const __bf16*)p.v.ptr + b * p.v.sb + hk * p.v.sh;
-
   // Q as the B operand of S^T = K Q^T: lane holds Q[row][16*ks + 8h .. +7]
   bf16x8 qreg[DK];
   const int row = min(q_w0 + r, sq - 1);
@@ -60,40 +57,44 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
   float m_run = -INFINITY, l_run = 0.f;
   const float c = p.scale * kLog2e;
 
-  const int n_tiles = (sk + BK - 1) / BK;
-  auto next_tile = [&](int t) {
-    while (t < n_tiles && classify(mk, q_blk0, q_blk1, t * BK, min(t * BK + BK, sk), false) == TILE_SKIP) ++t;
-    return t;
-  };
+  // Key tiles the work-group can see, and the class of each against this wave's 32 query rows
+  int qlo_blk, qhi_blk, qlo_w = 0, qhi_w = 0;
+  range_minmax(q_blk0, q_blk1, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, qlo_blk, qhi_blk);
+  if (q_w0 < q_w1) range_minmax(q_w0, q_w1, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, qlo_w, qhi_w);
+  BlockClassifier<false> k_class;
+  k_class.init(mk, qlo_w, qhi_w, sk, q_w0 >= q_w1);
+  auto tile_class = [&](int k0_) { return k_class(mk, k0_, min(k0_ + BK, sk), k0_ + BK > sk); };   // wave-uniform
 
-  TileStager<D, BK, NT> stage_k, stage_v;
-  stage_k.init(p.k.ss, tid);
-  stage_v.init(p.v.ss, tid);
+  KvWalk<D, BK, NT> walk;
+  walk.init(mk, p.k, p.v, b, hk, sk, qhi_blk, tid);
   wait_global_loads();
-  int t = next_tile(0);
-  if (t < n_tiles) {
-    stage_k.load(kg, p.k.ss, t * BK, sk, tid);
-    stage_v.load(vg, p.v.ss, t * BK, sk, tid);
-    stage_k.store(smem);
-    stage_v.store(smem + TILE);
+  int k0 = 0, cls = TILE_SKIP;   // first key row and class of the tile in LDS
+  if (walk.n_tiles > 0) {
+    walk.issue(tid);
+    walk.commit(smem, smem + TILE);
+    k0 = walk.k0;
+    cls = tile_class(k0);
+    walk.advance();
   }
   __syncthreads();
   int buf = 0;
-  while (t < n_tiles) {
-    const int tn = next_tile(t + 1);
-    if (tn < n_tiles) {
-      stage_k.load(kg, p.k.ss, tn * BK, sk, tid);
-      stage_v.load(vg, p.v.ss, tn * BK, sk, tid);
+  for (int it = 0; it < walk.n_tiles; ++it) {
+    const bool more = it + 1 < walk.n_tiles;
+    int k0n = 0, cls_n = TILE_SKIP;
+    if (more) {
+      walk.issue(tid);
+      k0n = walk.k0;
+      cls_n = tile_class(k0n);
+      walk.advance();
     }
     const char* kt = smem + buf * 2 * TILE;
     const char* vt = kt + TILE;
-    const int cls = classify(mk, q_w0, q_w1, t * BK, min(t * BK + BK, sk), t * BK + BK > sk);   // wave-uniform
     if (cls != TILE_SKIP) {
       f32x16 s[KB];
       gemm_rows<PITCH, KB, DK, kRowsAhead, true>(kt, 0, qreg, s, r, h);
       if (cls == TILE_PARTIAL) {
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) mask_tile<true>(s[kb], mk, t * BK + kb * 32 + 4 * h, sk, qpos);
+        for (int kb = 0; kb < KB; ++kb) mask_tile<true>(s[kb], mk, k0 + kb * 32 + 4 * h, sk, qpos);
       }
       float mx = s[0][0];
 #pragma unroll
@@ -143,14 +144,11 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
         }
       }
     }
-    if (tn < n_tiles) {
-      char* nk = smem + (buf ^ 1) * 2 * TILE;
-      stage_k.store(nk);
-      stage_v.store(nk + TILE);
-    }
+    if (more) walk.commit(smem + (buf ^ 1) * 2 * TILE, smem + (buf ^ 1) * 2 * TILE + TILE);
     __syncthreads();
-    t = tn;
     buf ^= 1;
+    k0 = k0n;
+    cls = cls_n;
   }
 
   // Epilogue: normalise, Lse in natural-log units, optional online-softmax merge.
