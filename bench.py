@@ -22,28 +22,39 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
 
+# HBM bytes per launch of the dominant kernel from the FETCH_SIZE / WRITE_SIZE counter runs of this
+# command (profiles/bench_config2_pmc_hbm_traffic.md: counter means over the ring, scaled by what the
+# same counters read for the 1 GiB copy issued below).  Counters cannot be read from inside the
+# process, so the figure is the profiled one and exists for the profiled workload only.
+PROFILED_TRAFFIC_BYTES = {2: 2.008e9}
 
-def cpu_baseline(w, kind, dev_i, shard_j, sample_rows, seed):
+
+def cpu_baseline(w, kind, dev_i, shards, sample_rows, seed):
     """The fp64 oracle, untuned, on a bounded sample of the same workload: `sample_rows` query rows
-    (evenly spaced over the chunk) of one (batch, head) against one whole KV shard, forward step +
-    backward step.  Returns TFLOPS with the same unmasked-FLOP count."""
+    (evenly spaced over the chunk) of one (batch, head) against each of the whole KV shards in
+    `shards`, forward step + D + backward step per shard.  Returns TFLOPS with the same
+    unmasked-FLOP count."""
     import numpy as np
     from oracle import burst_oracle as oc
     from paper_2509_19836_amd import workloads as wl
     G, N, d = w.shards, w.seq, w.head_dim
     pos_fn = {"zigzag": oc.zigzag_positions, "full": oc.contiguous_positions, "causal": oc.contiguous_positions}[kind]
-    qpos_all, kpos = pos_fn(dev_i, G, N), pos_fn(shard_j, G, N)
+    qpos_all = pos_fn(dev_i, G, N)
     sel = np.linspace(0, qpos_all.size - 1, sample_rows).astype(np.int64)
     rng = np.random.Generator(np.random.PCG64(seed))
     draw = lambda n: wl.bf16_bits_to_f64(wl.f32_to_bf16_bits(rng.standard_normal((n, d), dtype=np.float32)))
-    Q, dO, K, V = draw(sample_rows), draw(sample_rows), draw(kpos.size), draw(kpos.size)
-    vis = oc.visibility(qpos_all[sel], kpos, kind != "full")
-    pairs = int(vis.sum())
-    t0 = time.perf_counter()
-    O, lse = oc.step_fwd(Q, K, V, w.scale, vis)
-    D = oc.preprocess_bwd(dO, O)
-    oc.step_bwd(Q, K, V, dO, lse, D, w.scale, vis)
-    dt = time.perf_counter() - t0
+    Q, dO = draw(sample_rows), draw(sample_rows)
+    pairs, dt = 0, 0.0
+    for shard_j in shards:
+        kpos = pos_fn(shard_j, G, N)
+        K, V = draw(kpos.size), draw(kpos.size)
+        vis = oc.visibility(qpos_all[sel], kpos, kind != "full")
+        pairs += int(vis.sum())
+        t0 = time.perf_counter()
+        O, lse = oc.step_fwd(Q, K, V, w.scale, vis)
+        D = oc.preprocess_bwd(dO, O)
+        oc.step_bwd(Q, K, V, dO, lse, D, w.scale, vis)
+        dt += time.perf_counter() - t0
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
@@ -51,9 +62,9 @@ def cpu_baseline(w, kind, dev_i, shard_j, sample_rows, seed):
         cores = os.cpu_count()
     return {"value": pairs * 14 * d / dt / 1e12, "unit": "TFLOPS", "cores": int(cores), "kind": "oracle",
             "seconds": round(dt, 3),
-            "sample": f"{sample_rows} evenly spaced query rows of one (batch, head) against one full "
-                      f"{kpos.size}-row KV shard (device {dev_i} vs shard {shard_j}, {kind}), forward step "
-                      f"+ D + backward step in fp64 numpy; {pairs} visible pairs"}
+            "sample": f"{sample_rows} evenly spaced query rows of one (batch, head) against {len(shards)} full "
+                      f"{N // G}-row KV shards (device {dev_i} vs shards {list(shards)}, {kind}), forward step "
+                      f"+ D + backward step per shard in fp64 numpy; {pairs} visible pairs"}
 
 
 def main():
@@ -64,6 +75,7 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload index (1-5) of the benchmark definition")
     ap.add_argument("--device-index", type=int, default=3, help="which simulated device's ring to run")
     ap.add_argument("--cpu-sample-rows", type=int, default=16384)
+    ap.add_argument("--cpu-shards", type=int, default=4, help="KV shards the CPU baseline sample covers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -197,11 +209,12 @@ def main():
         "pct_of_random_operand_mfma_ceiling": round(100 * value / ceiling["random_operands"], 2),
         "roofline": {"bound": "mfma", "kernel": "step_bwd_dkdv_kernel", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None,
+                     "traffic": PROFILED_TRAFFIC_BYTES.get(args.config) if i == 3 else None,
                      "issued_tflops": round(per_launch_pairs * 8 * d / (avg["step_bwd_dkdv"] * 1e-3) / 1e12, 2)},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, kind, i, order[1 % G], args.cpu_sample_rows, wl.BASE_SEED + 5)
+        out["cpu_baseline"] = cpu_baseline(w, kind, i, order[1:1 + args.cpu_shards] or order[:1], args.cpu_sample_rows,
+                                           wl.BASE_SEED + 5)
     print(json.dumps(out))
 
 
