@@ -31,7 +31,8 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
   if (!bm.valid) return;
   const int b = bm.key / p.kv_heads, hk = bm.key - b * p.kv_heads, hq = hk * group + bm.head_in_group;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, h = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: everything derived from it stays wave-uniform
   const int sq = p.sq, sk = p.sk;
   const MaskDev mk = p.mask;
   const int q_blk0 = p.q_runs.tile_of(bm.tile) * BQ;     // first row of the work-group
