@@ -116,6 +116,8 @@ def main():
     DQ, DKV = lib.BURST_ACC_DQ, lib.BURST_ACC_DK | lib.BURST_ACC_DV
     ev = lambda: torch.cuda.Event(enable_timing=True)
     spans = {"step_fwd": [], "step_bwd_dq": [], "step_bwd_dkdv": [], "preprocess_bwd": []}
+    by_kind = {}   # (kernel, kind of ring step) -> durations; kinds: the shard's own chunk, an earlier one, a later one
+    kind_of = lambda j: "diag" if j == i else ("j<i" if j < i else "j>i")
 
     def reset():   # outside the timed region
         o_acc.zero_()
@@ -126,22 +128,22 @@ def main():
 
     def one_ring(record):
         marks = []
-        def span(name, fn):
+        def span(name, j, fn):
             if record:
                 a, b = ev(), ev()
                 a.record(); fn(); b.record()
-                marks.append((name, a, b))
+                marks.append((name, j, a, b))
             else:
                 fn()
         for j in order:
-            span("step_fwd", lambda: lib.burst_attn_step_fwd(shp, masks[j], q_i, ks[j], vs[j], o_acc=o_acc, lse_acc=lse_acc))
-        span("preprocess_bwd", lambda: lib.burst_attn_preprocess_bwd(shp, o_acc, do_i, d_i))
+            span("step_fwd", j, lambda: lib.burst_attn_step_fwd(shp, masks[j], q_i, ks[j], vs[j], o_acc=o_acc, lse_acc=lse_acc))
+        span("preprocess_bwd", None, lambda: lib.burst_attn_preprocess_bwd(shp, o_acc, do_i, d_i))
         for j in order:
             # the two launches burst_attn_step_bwd makes for (dq, dk, dv), bracketed one by one
-            span("step_bwd_dq", lambda: lib.burst_attn_step_bwd(shp, masks[j], q_i, ks[j], vs[j], do_i, lse_acc, d_i,
-                                                               dq=dq, accumulate_flags=DQ))
-            span("step_bwd_dkdv", lambda: lib.burst_attn_step_bwd(shp, masks[j], q_i, ks[j], vs[j], do_i, lse_acc, d_i,
-                                                                 dk=dks[j], dv=dvs[j], accumulate_flags=DKV))
+            span("step_bwd_dq", j, lambda: lib.burst_attn_step_bwd(shp, masks[j], q_i, ks[j], vs[j], do_i, lse_acc, d_i,
+                                                                  dq=dq, accumulate_flags=DQ))
+            span("step_bwd_dkdv", j, lambda: lib.burst_attn_step_bwd(shp, masks[j], q_i, ks[j], vs[j], do_i, lse_acc, d_i,
+                                                                    dk=dks[j], dv=dvs[j], accumulate_flags=DKV))
         return marks
 
     # The running state and the gradient accumulators are initialised once; later rings keep
@@ -156,8 +158,11 @@ def main():
         all_marks += one_ring(True)
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t0
-    for name, a, b in all_marks:
-        spans[name].append(a.elapsed_time(b))
+    for name, j, a, b in all_marks:
+        ms = a.elapsed_time(b)
+        spans[name].append(ms)
+        if j is not None:
+            by_kind.setdefault((name, kind_of(j)), []).append(ms)
     assert torch.isfinite(o_acc).all() and torch.isfinite(dq).all(), "non-finite result"
 
     # Outside the timed region: (1) the matrix-core ceiling of this chip as clocked under load, with
@@ -192,6 +197,23 @@ def main():
     per_launch_pairs = sum(pairs.values()) / G * B * Hq
     dom_flops = per_launch_pairs * 6 * d
     achieved = dom_flops / (avg["step_bwd_dkdv"] * 1e-3) / 1e12
+    # The kinds of ring step timed separately: TFLOPS of a whole step (fwd + dq + dkdv launches) from the
+    # median duration of each launch, with that step's own visible-pair count.
+    med = lambda v: sorted(v)[len(v) // 2]
+    step_kinds = {}
+    for kind_ in ("diag", "j<i", "j>i"):
+        js = [j for j in order if kind_of(j) == kind_]
+        if not js:
+            continue
+        f_ms, q_ms, kv_ms = (med(by_kind[(n_, kind_)]) for n_ in ("step_fwd", "step_bwd_dq", "step_bwd_dkdv"))
+        step_pairs = pairs[js[0]] * B * Hq
+        step_kinds[kind_] = {"steps_per_ring": len(js), "fwd_ms": round(f_ms, 4), "bwd_dq_ms": round(q_ms, 4),
+                             "bwd_dkdv_ms": round(kv_ms, 4),
+                             "fwd_tflops": round(step_pairs * 4 * d / (f_ms * 1e-3) / 1e12, 1),
+                             "bwd_tflops": round(step_pairs * 10 * d / ((q_ms + kv_ms) * 1e-3) / 1e12, 1),
+                             "fwd_bwd_tflops": round(step_pairs * 14 * d / ((f_ms + q_ms + kv_ms) * 1e-3) / 1e12, 1)}
+    # D = rowsum(dO o O) is bound by HBM: it reads O (fp32) and dO (bf16) once and writes one float per row
+    pre_bytes = B * n * Hq * (d * 6 + 4)
     out = {
         "metric": "attention fwd+bwd TFLOPS per ring step (unmasked FLOPs)",
         "value": round(value, 2), "unit": "TFLOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -205,6 +227,9 @@ def main():
         "fwd_tflops": round(fl_fwd / (fwd_ms * 1e-3) / 1e12, 2),
         "bwd_tflops": round(fl_bwd / (bwd_ms * 1e-3) / 1e12, 2),
         "kernel_ms": {k: round(v, 4) for k, v in avg.items()},
+        "kernel_ms_min": {k: round(min(v), 4) for k, v in spans.items() if v},
+        "step_kinds": step_kinds,
+        "preprocess_bwd_gb_s": round(pre_bytes / (avg["preprocess_bwd"] * 1e-3) / 1e9, 1),
         "mfma_ceiling_tflops": {k: round(v, 1) for k, v in ceiling.items()},
         "pct_of_random_operand_mfma_ceiling": round(100 * value / ceiling["random_operands"], 2),
         "roofline": {"bound": "mfma", "kernel": "step_bwd_dkdv_kernel", "achieved": round(achieved, 2),
