@@ -64,6 +64,10 @@ for _name in ("zigzag", "contiguous", "striped"):
     _f.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int32, _P(burst_mask_t)]
 _lib.burst_attn_visible_pairs.restype = C.c_int64
 _lib.burst_attn_visible_pairs.argtypes = [_P(burst_mask_t)]
+_lib.burst_attn_tile_class.restype = C.c_int
+_lib.burst_attn_tile_class.argtypes = [_P(burst_mask_t)] + [C.c_int64] * 4 + [C.c_int32]
+_lib.burst_attn_visible_tile_runs.restype = C.c_int
+_lib.burst_attn_visible_tile_runs.argtypes = [_P(burst_mask_t), C.c_int32, C.c_int32, C.c_int64, C.c_int64, _P(C.c_int32 * 4)]
 _lib.burst_attn_mfma_probe.restype = C.c_int
 _lib.burst_attn_mfma_probe.argtypes = [C.c_int32, C.c_int32, C.c_void_p, _P(C.c_int64), C.c_void_p]
 _lib.burst_attn_status_string.restype = C.c_char_p
@@ -73,7 +77,7 @@ _lib.burst_attn_version.restype = C.c_char_p
 
 EXPORTS = ["burst_attn_step_fwd", "burst_attn_lse_merge", "burst_attn_preprocess_bwd", "burst_attn_step_bwd",
            "burst_attn_fill_zigzag_mask", "burst_attn_fill_contiguous_mask", "burst_attn_fill_striped_mask",
-           "burst_attn_visible_pairs", "burst_attn_mfma_probe", "burst_attn_status_string", "burst_attn_last_hip_error",
+           "burst_attn_visible_pairs", "burst_attn_tile_class", "burst_attn_visible_tile_runs", "burst_attn_mfma_probe", "burst_attn_status_string", "burst_attn_last_hip_error",
            "burst_attn_version"]
 
 
@@ -142,6 +146,20 @@ def burst_attn_fill_striped_mask(dev_i, shard_j, G, N, causal=True):
 
 def burst_attn_visible_pairs(mask):
     return _lib.burst_attn_visible_pairs(C.byref(mask))
+
+
+def burst_attn_tile_class(mask, q0, q1, k0, k1, method=0):
+    st = _lib.burst_attn_tile_class(C.byref(mask), q0, q1, k0, k1, method)
+    if st < 0:
+        raise BurstError(st)
+    return st
+
+
+def burst_attn_visible_tile_runs(mask, query_axis, tile_rows, r0, r1):
+    """Runs of tiles as [(start, length), (start, length)]."""
+    out = (C.c_int32 * 4)()
+    _check(_lib.burst_attn_visible_tile_runs(C.byref(mask), int(query_axis), tile_rows, r0, r1, C.byref(out)))
+    return [(out[0], out[1]), (out[2], out[3])]
 
 
 def burst_attn_version():

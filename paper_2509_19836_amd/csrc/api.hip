@@ -300,6 +300,58 @@ int64_t burst_attn_visible_pairs(const burst_mask_t* m) {
   return total;
 }
 
+// The tile logic of the kernels, run on the host with the code the kernels compile.
+int burst_attn_tile_class(const burst_mask_t* mask, int64_t q0, int64_t q1, int64_t k0, int64_t k1, int32_t method) {
+  if (!mask) return BURST_ERR_INVALID_ARG;
+  const int64_t sq = mask->q_nseg * mask->q_seg_len, sk = mask->k_nseg * mask->k_seg_len;
+  MaskDev mk;
+  BURST_TRY(check_mask(mask, sq, sk, &mk));
+  if (q0 < 0 || q1 > sq || q0 >= q1 || k0 < 0 || k1 > sk || k0 >= k1) return BURST_ERR_INVALID_ARG;
+  if (method == 0) return classify(mk, (int)q0, (int)q1, (int)k0, (int)k1, false);
+  int lo, hi;
+  if (method == 1) {   // query block against a fixed key range
+    range_minmax((int)k0, (int)k1, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride, lo, hi);
+    BlockClassifier<true> c;
+    c.init(mk, lo, hi, (int)sq, false);
+    return c(mk, (int)q0, (int)q1, false);
+  }
+  if (method == 2) {   // key block against a fixed query range
+    range_minmax((int)q0, (int)q1, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, lo, hi);
+    BlockClassifier<false> c;
+    c.init(mk, lo, hi, (int)sk, false);
+    return c(mk, (int)k0, (int)k1, false);
+  }
+  return BURST_ERR_INVALID_ARG;
+}
+
+int burst_attn_visible_tile_runs(const burst_mask_t* mask, int32_t query_axis, int32_t tile_rows, int64_t r0, int64_t r1,
+                                 int32_t out_start_len[4]) {
+  if (!mask || !out_start_len) return BURST_ERR_INVALID_ARG;
+  const int64_t sq = mask->q_nseg * mask->q_seg_len, sk = mask->k_nseg * mask->k_seg_len;
+  MaskDev mk;
+  BURST_TRY(check_mask(mask, sq, sk, &mk));
+  const int64_t other = query_axis ? sk : sq;
+  if (r0 < 0 || r1 > other || r0 >= r1) return BURST_ERR_INVALID_ARG;
+  int lo, hi;
+  TileRuns tr;
+  if (query_axis) {
+    range_minmax((int)r0, (int)r1, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride, lo, hi);
+    if (tile_rows == 64) tr = visible_tiles<true, 64>(mk, lo, (int)sq);
+    else if (tile_rows == 256) tr = visible_tiles<true, 256>(mk, lo, (int)sq);
+    else return BURST_ERR_UNSUPPORTED;
+  } else {
+    range_minmax((int)r0, (int)r1, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, lo, hi);
+    if (tile_rows == 64) tr = visible_tiles<false, 64>(mk, hi, (int)sk);
+    else if (tile_rows == 128) tr = visible_tiles<false, 128>(mk, hi, (int)sk);
+    else return BURST_ERR_UNSUPPORTED;
+  }
+  out_start_len[0] = tr.start[0];
+  out_start_len[1] = tr.len[0];
+  out_start_len[2] = tr.start[1];
+  out_start_len[3] = tr.len[1];
+  return BURST_OK;
+}
+
 int burst_attn_mfma_probe(int32_t random_operands, int32_t iterations, float* sink, int64_t* flops_out,
                           void* hip_stream) {
   if (iterations < 1 || iterations > (1 << 24)) return BURST_ERR_INVALID_ARG;

@@ -172,3 +172,91 @@ def test_workload_generators_are_seeded_and_exact():
     t4 = wl.host_tensors(w4, 4)
     stds = t4["q"][0].std(axis=(1, 3))
     assert stds.min() > 0.4 and stds.max() < 2.2 and stds.std() > 0.05
+
+
+def _custom_mask(lib, q_pos, k_pos, q_len, k_len, stride, causal=True):
+    m = lib.burst_mask_t()
+    m.mode = lib.BURST_MASK_CAUSAL if causal else lib.BURST_MASK_FULL
+    m.q_nseg, m.k_nseg = len(q_pos), len(k_pos)
+    for s, p in enumerate(q_pos):
+        m.q_seg_pos[s] = p
+    for s, p in enumerate(k_pos):
+        m.k_seg_pos[s] = p
+    m.q_seg_len, m.k_seg_len, m.pos_stride = q_len, k_len, stride
+    return m
+
+
+def _tile_logic_masks(lib):
+    """Masks with segment lengths that are and are not multiples of the tile sizes, one and two
+    segments per axis, unit and larger position strides, segments in either position order."""
+    out = []
+    for G, N in ((2, 2 * 2 * 160), (4, 4 * 2 * 96), (3, 3 * 2 * 100)):
+        for i in range(G):
+            for j in range(G):
+                out.append(lib.burst_attn_fill_zigzag_mask(i, j, G, N))
+    for G, N in ((2, 2 * 300), (4, 4 * 256)):
+        for i in range(G):
+            for j in range(G):
+                out.append(lib.burst_attn_fill_contiguous_mask(i, j, G, N))
+                out.append(lib.burst_attn_fill_striped_mask(i, j, G, N))
+    out.append(_custom_mask(lib, (700, 10), (300, 0), 150, 170, 1))     # second segment earlier than the first
+    out.append(_custom_mask(lib, (5, 900), (0,), 130, 400, 3))          # stride 3, mixed segment counts
+    out.append(_custom_mask(lib, (40,), (0, 1000), 333, 200, 2))
+    out.append(_custom_mask(lib, (0, 512), (0, 512), 256, 256, 1, causal=False))
+    return out
+
+
+def test_tile_classes_match_brute_force(lib):
+    """Every (query block, key block) class the kernels can compute, by all three methods, against
+    the visibility matrix of the oracle: skip <=> no visible pair, full <=> all pairs visible."""
+    rng = np.random.default_rng(7)
+    for m in _tile_logic_masks(lib):
+        qpos, kpos = hp.mask_positions(m, "q"), hp.mask_positions(m, "k")
+        vis = oc.visibility(qpos, kpos, m.mode == lib.BURST_MASK_CAUSAL)
+        sq, sk = qpos.size, kpos.size
+        blocks = [(q0, min(q0 + bq, sq), k0, min(k0 + bk, sk))
+                  for bq, bk in ((64, 128), (256, 64), (32, 64), (64, 32))
+                  for q0 in range(0, sq, bq) for k0 in range(0, sk, bk)]
+        for q0, q1, k0, k1 in [blocks[t] for t in rng.permutation(len(blocks))[:120]]:
+            sub = vis[q0:q1, k0:k1]
+            want = 0 if not sub.any() else (1 if sub.all() else 2)
+            for method in (0, 1, 2):
+                assert lib.burst_attn_tile_class(m, q0, q1, k0, k1, method) == want, (q0, q1, k0, k1, method)
+
+
+def test_visible_tile_runs_match_brute_force(lib):
+    """The closed-form runs of tiles a kernel walks hold exactly the tiles with a visible pair."""
+    rng = np.random.default_rng(11)
+    for m in _tile_logic_masks(lib):
+        qpos, kpos = hp.mask_positions(m, "q"), hp.mask_positions(m, "k")
+        vis = oc.visibility(qpos, kpos, m.mode == lib.BURST_MASK_CAUSAL)
+        sq, sk = qpos.size, kpos.size
+        for query_axis, tile, other_block in ((1, 64, 128), (1, 256, 128), (0, 64, 256), (0, 128, 256)):
+            rows, other = (sq, sk) if query_axis else (sk, sq)
+            for r0 in rng.permutation(np.arange(0, other, other_block))[:6]:
+                r0, r1 = int(r0), int(min(r0 + other_block, other))
+                sub = vis[:, r0:r1] if query_axis else vis[r0:r1, :].T     # [rows of the walked axis, other rows]
+                n_tiles = -(-rows // tile)
+                want = [bool(sub[t * tile:(t + 1) * tile].any()) for t in range(n_tiles)]
+                runs = lib.burst_attn_visible_tile_runs(m, query_axis, tile, r0, r1)
+                got = [False] * n_tiles
+                prev_end = 0
+                for start, length in runs:
+                    if length:
+                        assert start >= prev_end and start + length <= n_tiles
+                        prev_end = start + length
+                        for t in range(start, start + length):
+                            got[t] = True
+                assert got == want, (query_axis, tile, r0, r1, runs)
+
+
+def test_tile_logic_rejects_bad_arguments(lib):
+    m = lib.burst_attn_fill_zigzag_mask(1, 0, 2, 256)
+    raw = lib.raw()
+    assert raw.burst_attn_tile_class(None, 0, 1, 0, 1, 0) == lib.BURST_ERR_INVALID_ARG
+    assert raw.burst_attn_tile_class(C.byref(m), 0, 0, 0, 1, 0) == lib.BURST_ERR_INVALID_ARG
+    assert raw.burst_attn_tile_class(C.byref(m), 0, 1, 0, 1000, 0) == lib.BURST_ERR_INVALID_ARG
+    assert raw.burst_attn_tile_class(C.byref(m), 0, 1, 0, 1, 9) == lib.BURST_ERR_INVALID_ARG
+    out = (C.c_int32 * 4)()
+    assert raw.burst_attn_visible_tile_runs(C.byref(m), 1, 48, 0, 1, C.byref(out)) == lib.BURST_ERR_UNSUPPORTED
+    assert raw.burst_attn_visible_tile_runs(C.byref(m), 1, 64, 5, 5, C.byref(out)) == lib.BURST_ERR_INVALID_ARG

@@ -161,3 +161,17 @@ def test_empty_chunks(lib):
     shp = lib.shape(B, H, H, d, 0, 16, 0.125)
     lib.burst_attn_step_fwd(shp, None, q, kv, kv, o_part=o_part, lse_part=lse_part)
     torch.cuda.synchronize()
+
+
+@pytest.mark.gpu
+def test_mfma_probe_runs_and_counts_its_flops(lib):
+    """The matrix-core ceiling probe: argument checks on the host, a short launch of each operand kind
+    completes, and the flop count is that of the launch (512 work-groups x 4 waves x 4 chains)."""
+    import torch
+    raw = lib.raw()
+    import ctypes as C
+    assert raw.burst_attn_mfma_probe(0, 0, None, None, None) == lib.BURST_ERR_INVALID_ARG
+    for random_operands in (0, 1):
+        flops = lib.burst_attn_mfma_probe(random_operands, 100)
+        torch.cuda.synchronize()
+        assert flops == 512 * 4 * 4 * 100 * 2 * 32 * 32 * 16
