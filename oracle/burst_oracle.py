@@ -57,14 +57,25 @@ def striped_positions(i, G, N):
     return np.arange(i, N, G, dtype=np.int64)
 
 
-def visibility(pos_q, pos_k, causal):
+def visibility(pos_q, pos_k, causal, window=0):
     """Boolean [len(pos_q), len(pos_k)]: may query row r use key row c?
-    Causal (Eq. 10): a token attends to keys 1..i, itself included."""
+    Causal (Eq. 10): a token attends to keys 1..i, itself included.
+    window > 0 (sliding-window attention, the sparse pattern of Sec. 3.4 /
+    the SWA row of the sparse-attention table): of those keys only the last
+    `window` positions, i.e. keys at positions p-window+1 .. p for a query at
+    position p.  The paper states no formula for the window; this is the
+    usual definition, with the token itself counted in the window."""
     pos_q = np.asarray(pos_q, dtype=np.int64)
     pos_k = np.asarray(pos_k, dtype=np.int64)
     if not causal:
+        if window:
+            raise ValueError("a window needs a causal mask")
         return np.ones((pos_q.size, pos_k.size), dtype=bool)
-    return pos_q[:, None] >= pos_k[None, :]
+    diff = pos_q[:, None] - pos_k[None, :]
+    vis = diff >= 0
+    if window:
+        vis &= diff < window
+    return vis
 
 
 # ---------------------------------------------------------------------------
@@ -367,5 +378,5 @@ def mha_attention_bwd(Q, K, V, dO, scale, vis=None):
 # Work counting (the benchmark's FLOP convention): visible (q, k) pairs.
 # ---------------------------------------------------------------------------
 
-def visible_pairs(pos_q, pos_k, causal):
-    return int(visibility(pos_q, pos_k, causal).sum())
+def visible_pairs(pos_q, pos_k, causal, window=0):
+    return int(visibility(pos_q, pos_k, causal, window).sum())

@@ -417,6 +417,85 @@ def test_against_torch_sdpa_float64_autograd():
         assert np.abs(tv.grad.numpy() - dV).max() < 1e-12
 
 
+# ----------------------------------------------------------------- sliding window
+
+@pytest.mark.parametrize("window", [1, 2, 5, 16, 100])
+def test_window_visibility_brute_force_and_limits(window):
+    """A query at position p sees exactly the keys at positions p-window+1 .. p: brute force over
+    scattered positions; a window of one leaves the token itself (O = its V row, lse = its score);
+    a window as long as the sequence is plain causal attention."""
+    pos_q = np.array([0, 3, 4, 9, 17, 18, 40])
+    pos_k = np.array([0, 1, 4, 8, 9, 16, 18, 39, 40, 41])
+    vis = oc.visibility(pos_q, pos_k, True, window)
+    for a, p in enumerate(pos_q):
+        for b, k in enumerate(pos_k):
+            assert vis[a, b] == (p - window + 1 <= k <= p)
+    assert oc.visible_pairs(pos_q, pos_k, True, window) == int(vis.sum())
+    n, d = 12, 4
+    Q, K, V, _ = rand_qkvdo(70, n, n, d)
+    pos = np.arange(n)
+    if window == 1:
+        O, lse = oc.attention_fwd(Q, K, V, 0.5, oc.visibility(pos, pos, True, 1))
+        assert np.allclose(O, V, atol=1e-14)
+        assert np.allclose(lse, 0.5 * (Q * K).sum(1), atol=1e-13)
+    if window >= n:
+        assert (oc.visibility(pos, pos, True, window) == oc.visibility(pos, pos, True)).all()
+    with pytest.raises(ValueError):
+        oc.visibility(pos, pos, False, window)
+
+
+@pytest.mark.parametrize("part", ["contiguous", "zigzag", "striped"])
+def test_windowed_ring_equals_unsharded_windowed_attention(part):
+    """Forward ring + merge and both backward travel orders over windowed step masks reproduce
+    unsharded sliding-window attention; steps wholly outside the window contribute (0, -inf)."""
+    G, N, d, window, scale = 4, 48, 4, 10, 0.4
+    pos_fn = {"contiguous": oc.contiguous_positions, "zigzag": oc.zigzag_positions, "striped": oc.striped_positions}[part]
+    Q, K, V, dO = rand_qkvdo(71, N, N, d)
+    allpos = np.arange(N)
+    vis_all = oc.visibility(allpos, allpos, True, window)
+    O_ref, lse_ref = oc.attention_fwd(Q, K, V, scale, vis_all)
+    dQ_ref, dK_ref, dV_ref = oc.attention_bwd(Q, K, V, dO, scale, vis_all)
+    pos = [pos_fn(i, G, N) for i in range(G)]
+    dK_tot, dV_tot = np.zeros_like(K), np.zeros_like(V)
+    saw_empty_step = False
+    for i in range(G):
+        order = oc.ring_order(i, G)
+        vis_of = lambda j: oc.visibility(pos[i], pos[j], True, window)
+        saw_empty_step |= any(not vis_of(j).any() for j in order)
+        O_i, lse_i = oc.ring_fwd(Q[pos[i]], [K[p] for p in pos], [V[p] for p in pos], scale, vis_of, order)
+        assert np.abs(O_i - O_ref[pos[i]]).max() < 1e-12
+        assert np.abs(lse_i - lse_ref[pos[i]]).max() < 1e-12
+        D_i = oc.preprocess_bwd(dO[pos[i]], O_i)
+        dQ_i = np.zeros((pos[i].size, d))
+        for j in order:
+            dq, dk, dv = oc.step_bwd(Q[pos[i]], K[pos[j]], V[pos[j]], dO[pos[i]], lse_i, D_i, scale, vis_of(j))
+            dQ_i += dq
+            dK_tot[pos[j]] += dk
+            dV_tot[pos[j]] += dv
+        assert np.abs(dQ_i - dQ_ref[pos[i]]).max() < 1e-12
+    assert np.abs(dK_tot - dK_ref).max() < 1e-12 and np.abs(dV_tot - dV_ref).max() < 1e-12
+    if part == "contiguous":
+        assert saw_empty_step   # N/G = 12 > window: shards two or more behind are out of reach
+
+
+def test_windowed_attention_against_torch_sdpa_mask():
+    torch = pytest.importorskip("torch")
+    S, d, window = 29, 8, 7
+    scale = 1.0 / math.sqrt(d)
+    Q, K, V, dO = rand_qkvdo(72, S, S, d)
+    vis = oc.visibility(np.arange(S), np.arange(S), True, window)
+    O, _ = oc.attention_fwd(Q, K, V, scale, vis)
+    dQ, dK, dV = oc.attention_bwd(Q, K, V, dO, scale, vis)
+    idx = torch.arange(S)
+    band = (idx[:, None] >= idx[None, :]) & (idx[:, None] - idx[None, :] < window)   # written out here, not taken from the oracle
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (Q, K, V))
+    out = torch.nn.functional.scaled_dot_product_attention(tq[None, None], tk[None, None], tv[None, None], attn_mask=band)[0, 0]
+    out.backward(torch.tensor(dO))
+    assert np.abs(out.detach().numpy() - O).max() < 1e-12
+    for got, want in ((tq.grad, dQ), (tk.grad, dK), (tv.grad, dV)):
+        assert np.abs(got.numpy() - want).max() < 1e-12
+
+
 # ----------------------------------------------------------------- planted mistakes are caught
 
 def test_planted_mistakes_fail_the_pins(monkeypatch):
