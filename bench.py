@@ -29,7 +29,7 @@ PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flo
 PROFILED_TRAFFIC_BYTES = {2: 2.008e9}
 
 
-def cpu_baseline(w, kind, dev_i, shards, sample_rows, seed):
+def cpu_baseline(w, kind, dev_i, shards, sample_rows, seed, window=0):
     """The fp64 oracle, untuned, on a bounded sample of the same workload: `sample_rows` query rows
     (evenly spaced over the chunk) of one (batch, head) against each of the whole KV shards in
     `shards`, forward step + D + backward step per shard.  Returns TFLOPS with the same
@@ -38,7 +38,8 @@ def cpu_baseline(w, kind, dev_i, shards, sample_rows, seed):
     from oracle import burst_oracle as oc
     from paper_2509_19836_amd import workloads as wl
     G, N, d = w.shards, w.seq, w.head_dim
-    pos_fn = {"zigzag": oc.zigzag_positions, "full": oc.contiguous_positions, "causal": oc.contiguous_positions}[kind]
+    pos_fn = {"zigzag": oc.zigzag_positions, "full": oc.contiguous_positions, "causal": oc.contiguous_positions,
+              "striped": oc.striped_positions}[kind]
     qpos_all = pos_fn(dev_i, G, N)
     sel = np.linspace(0, qpos_all.size - 1, sample_rows).astype(np.int64)
     rng = np.random.Generator(np.random.PCG64(seed))
@@ -48,7 +49,7 @@ def cpu_baseline(w, kind, dev_i, shards, sample_rows, seed):
     for shard_j in shards:
         kpos = pos_fn(shard_j, G, N)
         K, V = draw(kpos.size), draw(kpos.size)
-        vis = oc.visibility(qpos_all[sel], kpos, kind != "full")
+        vis = oc.visibility(qpos_all[sel], kpos, kind != "full", window)
         pairs += int(vis.sum())
         t0 = time.perf_counter()
         O, lse = oc.step_fwd(Q, K, V, w.scale, vis)
@@ -75,6 +76,10 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload index (1-5) of the benchmark definition")
     ap.add_argument("--device-index", type=int, default=3, help="which simulated device's ring to run")
     ap.add_argument("--cpu-sample-rows", type=int, default=16384)
+    ap.add_argument("--window", type=int, default=0, help="sliding-window attention: window in tokens (0 = none); "
+                                                           "not the headline metric, for the sparse rows")
+    ap.add_argument("--partition", default=None, choices=["zigzag", "striped", "causal", "full"],
+                    help="override the workload's partition / mask kind")
     ap.add_argument("--cpu-shards", type=int, default=4, help="KV shards the CPU baseline sample covers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -87,7 +92,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
     w = wl.WORKLOADS[args.config]
-    kind, G, N, i = w.mask, w.shards, w.seq, args.device_index % w.shards
+    kind, G, N, i = args.partition or w.mask, w.shards, w.seq, args.device_index % w.shards
     n, d, B, Hq, Hkv = w.shard_tokens, w.head_dim, w.batch, w.q_heads, w.kv_heads
 
     gen = torch.Generator(device="cuda")
@@ -110,7 +115,7 @@ def main():
     dvs = [torch.empty(B, n, Hkv, d, **f32) for _ in range(G)]
 
     order = ring.ring_order(i, G)
-    masks = {j: ring.fill_mask(kind, i, j, G, N) for j in order}
+    masks = {j: ring.fill_mask(kind, i, j, G, N, args.window) for j in order}
     pairs = {j: lib.burst_attn_visible_pairs(masks[j]) for j in order}
     shp = lib.shape(B, Hq, Hkv, d, n, n, w.scale)
     DQ, DKV = lib.BURST_ACC_DQ, lib.BURST_ACC_DK | lib.BURST_ACC_DV
@@ -221,7 +226,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name} (config {args.config}): device {i} of {G}, one full simulated ring = "
                                f"{G} fwd steps + D + {G} bwd steps, B={B} Hq={Hq} Hkv={Hkv} d={d}, "
-                               f"Q chunk {n} x {G} KV chunks of {n}, mask {kind}",
+                               f"Q chunk {n} x {G} KV chunks of {n}, mask {kind}" + (f", window {args.window}" if args.window else ""),
                    "ring_steps_per_step": G, "ms_per_ring_step": round(ms_ring / G, 3)},
         "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
         "fwd_tflops": round(fl_fwd / (fwd_ms * 1e-3) / 1e12, 2),
@@ -234,12 +239,12 @@ def main():
         "pct_of_random_operand_mfma_ceiling": round(100 * value / ceiling["random_operands"], 2),
         "roofline": {"bound": "mfma", "kernel": "step_bwd_dkdv_kernel", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": PROFILED_TRAFFIC_BYTES.get(args.config) if i == 3 else None,
+                     "traffic": PROFILED_TRAFFIC_BYTES.get(args.config) if (i == 3 and not args.window and not args.partition) else None,
                      "issued_tflops": round(per_launch_pairs * 8 * d / (avg["step_bwd_dkdv"] * 1e-3) / 1e12, 2)},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, kind, i, order[1:1 + args.cpu_shards] or order[:1], args.cpu_sample_rows,
-                                           wl.BASE_SEED + 5)
+                                           wl.BASE_SEED + 5, args.window)
     print(json.dumps(out))
 
 

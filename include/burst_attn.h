@@ -70,7 +70,9 @@ typedef struct {
  * and has global token position  seg_pos[s] + (r - s*seg_len) * pos_stride.
  *   FULL  : every pair is visible.
  *   CAUSAL: a pair is visible iff position(q) >= position(k)  (Eq. 10: a token attends to itself
- *           and to everything before it).
+ *           and to everything before it); with window > 0 also position(q) - position(k) < window
+ *           (sliding-window attention, the sparse pattern of Sec. 3.4: the token itself and the
+ *           window - 1 positions before it).  window = 0: no window.  A window needs mode CAUSAL.
  * The zigzag split (Eq. 11-12) is two segments (front piece, back piece); the contiguous split is
  * one; the striped split (Eq. 13-14) is one segment with pos_stride = G.
  * sq == q_nseg*q_seg_len and sk == k_nseg*k_seg_len must hold.
@@ -81,6 +83,7 @@ typedef struct {
   int64_t q_seg_pos[2], k_seg_pos[2];
   int64_t q_seg_len, k_seg_len;
   int64_t pos_stride;
+  int64_t window;
 } burst_mask_t;
 
 /*
@@ -146,7 +149,8 @@ int burst_attn_step_bwd(const burst_shape_t* shape, const burst_mask_t* mask,
 /* Mask of device dev_i's queries against shard_j's keys on a ring of G devices over N tokens.
  * zigzag (Eq. 11, 0-based): device i holds [i*P,(i+1)*P) and [N-(i+1)*P, N-i*P), P = N/(2G),
  * N must be a multiple of 2G.  contiguous: device i holds [i*N/G,(i+1)*N/G).  striped (Eq. 13):
- * device i holds tokens i + G*m.  causal = 0 gives a FULL mask with the same geometry. */
+ * device i holds tokens i + G*m.  causal = 0 gives a FULL mask with the same geometry.  The helpers
+ * leave window = 0; set out->window afterwards for sliding-window attention. */
 int burst_attn_fill_zigzag_mask(int32_t dev_i, int32_t shard_j, int32_t G, int64_t N, int32_t causal,
                                 burst_mask_t* out);
 int burst_attn_fill_contiguous_mask(int32_t dev_i, int32_t shard_j, int32_t G, int64_t N,

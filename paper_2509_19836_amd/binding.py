@@ -42,7 +42,8 @@ class burst_rowvec_t(C.Structure):
 class burst_mask_t(C.Structure):
     _fields_ = [("mode", C.c_int32), ("q_nseg", C.c_int32), ("k_nseg", C.c_int32), ("_pad", C.c_int32),
                 ("q_seg_pos", C.c_int64 * 2), ("k_seg_pos", C.c_int64 * 2),
-                ("q_seg_len", C.c_int64), ("k_seg_len", C.c_int64), ("pos_stride", C.c_int64)]
+                ("q_seg_len", C.c_int64), ("k_seg_len", C.c_int64), ("pos_stride", C.c_int64),
+                ("window", C.c_int64)]
 
 
 _P = C.POINTER

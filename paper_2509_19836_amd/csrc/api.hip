@@ -65,11 +65,13 @@ int check_mask(const burst_mask_t* m, int64_t sq, int64_t sk, MaskDev* out) {
     out->q_seg_len = (int32_t)sq;
     out->k_seg_len = (int32_t)sk;
     out->pos_stride = 1;
+    out->window = kNoWindow;
     return BURST_OK;
   }
   if (m->mode != BURST_MASK_FULL && m->mode != BURST_MASK_CAUSAL) return BURST_ERR_INVALID_ARG;
   if (m->q_nseg < 1 || m->q_nseg > 2 || m->k_nseg < 1 || m->k_nseg > 2) return BURST_ERR_INVALID_ARG;
   if (m->q_seg_len < 0 || m->k_seg_len < 0 || m->pos_stride < 1) return BURST_ERR_INVALID_ARG;
+  if (m->window < 0 || (m->window > 0 && m->mode != BURST_MASK_CAUSAL)) return BURST_ERR_INVALID_ARG;
   if (m->q_seg_len * m->q_nseg != sq || m->k_seg_len * m->k_nseg != sk) return BURST_ERR_INVALID_ARG;
   for (int s = 0; s < 2; ++s) {
     if (s < m->q_nseg) {
@@ -91,6 +93,7 @@ int check_mask(const burst_mask_t* m, int64_t sq, int64_t sk, MaskDev* out) {
     out->k_seg_pos[s] = (int32_t)(s < m->k_nseg ? m->k_seg_pos[s] : 0);
   }
   out->pos_stride = (int32_t)m->pos_stride;
+  out->window = (m->window == 0 || m->window >= kNoWindow) ? kNoWindow : (int32_t)m->window;
   return BURST_OK;
 }
 
@@ -279,7 +282,7 @@ int burst_attn_fill_striped_mask(int32_t dev_i, int32_t shard_j, int32_t G, int6
 
 int64_t burst_attn_visible_pairs(const burst_mask_t* m) {
   if (!m || m->q_nseg < 1 || m->q_nseg > 2 || m->k_nseg < 1 || m->k_nseg > 2 || m->q_seg_len < 0 ||
-      m->k_seg_len < 0 || m->pos_stride < 1)
+      m->k_seg_len < 0 || m->pos_stride < 1 || m->window < 0 || (m->window > 0 && m->mode != BURST_MASK_CAUSAL))
     return -1;
   if (m->mode == BURST_MASK_FULL) return m->q_nseg * m->q_seg_len * m->k_nseg * m->k_seg_len;
   if (m->mode != BURST_MASK_CAUSAL) return -1;
@@ -292,8 +295,16 @@ int64_t burst_attn_visible_pairs(const burst_mask_t* m) {
         // keys j with b + j*s <= a + i*s
         const int64_t diff = a + i * s - b;
         if (diff < 0) continue;
-        int64_t cnt = diff / s + 1;
+        int64_t cnt = diff / s + 1;                 // keys at or before the query
         if (cnt > m->k_seg_len) cnt = m->k_seg_len;
+        if (m->window > 0) {                         // minus those that have left its window
+          const int64_t out_of_reach = diff - m->window;   // keys j with b + j*s <= a + i*s - window
+          if (out_of_reach >= 0) {
+            int64_t gone = out_of_reach / s + 1;
+            if (gone > m->k_seg_len) gone = m->k_seg_len;
+            cnt -= gone;
+          }
+        }
         total += cnt;
       }
     }
@@ -336,13 +347,13 @@ int burst_attn_visible_tile_runs(const burst_mask_t* mask, int32_t query_axis, i
   TileRuns tr;
   if (query_axis) {
     range_minmax((int)r0, (int)r1, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride, lo, hi);
-    if (tile_rows == 64) tr = visible_tiles<true, 64>(mk, lo, (int)sq);
-    else if (tile_rows == 256) tr = visible_tiles<true, 256>(mk, lo, (int)sq);
+    if (tile_rows == 64) tr = visible_tiles<true, 64>(mk, lo, hi, (int)sq);
+    else if (tile_rows == 256) tr = visible_tiles<true, 256>(mk, lo, hi, (int)sq);
     else return BURST_ERR_UNSUPPORTED;
   } else {
     range_minmax((int)r0, (int)r1, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, lo, hi);
-    if (tile_rows == 64) tr = visible_tiles<false, 64>(mk, hi, (int)sk);
-    else if (tile_rows == 128) tr = visible_tiles<false, 128>(mk, hi, (int)sk);
+    if (tile_rows == 64) tr = visible_tiles<false, 64>(mk, lo, hi, (int)sk);
+    else if (tile_rows == 128) tr = visible_tiles<false, 128>(mk, lo, hi, (int)sk);
     else return BURST_ERR_UNSUPPORTED;
   }
   out_start_len[0] = tr.start[0];

@@ -86,7 +86,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_bwd_dq_kernel(B
   auto tile_class = [&](int k0_) { return k_class(mk, k0_, min(k0_ + BK, sk), k0_ + BK > sk); };   // wave-uniform
 
   KvWalk<D, BK, NT> walk;
-  walk.init(mk, p.k, p.v, b, hk, sk, qhi_blk, tid);
+  walk.init(mk, p.k, p.v, b, hk, sk, qlo_blk, qhi_blk, tid);
   wait_global_loads();
   int k0 = 0, cls = TILE_SKIP;   // first key row and class of the tile in LDS
   if (walk.n_tiles > 0) {
@@ -217,7 +217,7 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
   // pipeline runs across head boundaries.  The visible tiles of a head are one or two runs of
   // consecutive tiles; inside a run the cursor moves by adding constants, and only a run or head
   // change recomputes addresses.
-  const TileRuns qr = visible_tiles<true, BQ>(mk, klo_blk, sq);
+  const TileRuns qr = visible_tiles<true, BQ>(mk, klo_blk, khi_blk, sq);
   const int n_items = group * qr.total();
   int c_run = 0, c_left = qr.len[0], c_head = 0;   // cursor: run, tiles left in it, head of the group
   int q0n = qr.start[0] * BQ;                      // first row of the tile under the cursor

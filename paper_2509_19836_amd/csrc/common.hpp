@@ -46,7 +46,20 @@ struct MaskDev {
   int32_t q_seg_len, k_seg_len;
   int32_t q_seg_pos[2], k_seg_pos[2];
   int32_t pos_stride;
+  int32_t window;   // causal only: pos(q) - pos(k) < window as well; kNoWindow = unlimited
 };
+constexpr int32_t kNoWindow = 0x7fffffff;   // no position difference reaches it (positions < 2^31 - 1)
+
+// Rows r in [0, seg_len) of a segment with r * stride < gap / with r * stride <= room (64-bit: the
+// bounds may carry the window).
+__host__ __device__ __forceinline__ int rows_below(long long gap, int stride, int seg_len) {
+  const long long n = gap <= 0 ? 0 : (gap + stride - 1) / stride;
+  return n < seg_len ? (int)n : seg_len;
+}
+__host__ __device__ __forceinline__ int rows_upto(long long room, int stride, int seg_len) {
+  const long long n = room < 0 ? 0 : room / stride + 1;
+  return n < seg_len ? (int)n : seg_len;
+}
 
 // A [batch, seq, heads, D] tensor; strides in elements.
 struct TensorDev {
@@ -79,6 +92,15 @@ __host__ __device__ __forceinline__ void range_minmax(int row0, int row1, int ns
   }
 }
 
+// Class of a block whose query positions span [qlo, qhi] and key positions [klo, khi] under a causal
+// mask, from the bounding ranges alone (a mixed verdict is always safe).
+__host__ __device__ __forceinline__ int classify_ranges(const MaskDev& mk, int qlo, int qhi, int klo, int khi, bool ragged) {
+  if (qhi < klo) return TILE_SKIP;                                   // every key lies after every query
+  if ((long long)qlo - khi >= mk.window) return TILE_SKIP;           // every key has left every query's window
+  if (qlo >= khi && (long long)qhi - klo < mk.window && !ragged) return TILE_FULL;
+  return TILE_PARTIAL;
+}
+
 // Classify the block of query rows [q0, q1) against key rows [k0, k1) (both already clipped to the
 // chunk).  PARTIAL = needs the per-element predicate: the mask edge crosses the block, or the caller
 // says so because the register tile also covers rows beyond the end of a chunk.
@@ -88,9 +110,7 @@ __host__ __device__ __forceinline__ int classify(const MaskDev& mk, int q0, int 
   int qlo, qhi, klo, khi;
   range_minmax(q0, q1, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, qlo, qhi);
   range_minmax(k0, k1, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride, klo, khi);
-  if (qhi < klo) return TILE_SKIP;
-  if (qlo >= khi && !ragged) return TILE_FULL;
-  return TILE_PARTIAL;
+  return classify_ranges(mk, qlo, qhi, klo, khi, ragged);
 }
 
 // Class of the row block whose positions span [lo, hi] against rows of the other axis spanning
@@ -100,9 +120,7 @@ template <bool Q_ROWS>
 __host__ __device__ __forceinline__ int classify_range(const MaskDev& mk, int lo, int hi, int olo, int ohi, bool ragged) {
   if (!mk.causal) return ragged ? TILE_PARTIAL : TILE_FULL;
   const int qlo = Q_ROWS ? lo : olo, qhi = Q_ROWS ? hi : ohi, klo = Q_ROWS ? olo : lo, khi = Q_ROWS ? ohi : hi;
-  if (qhi < klo) return TILE_SKIP;
-  if (qlo >= khi && !ragged) return TILE_FULL;
-  return TILE_PARTIAL;
+  return classify_ranges(mk, qlo, qhi, klo, khi, ragged);
 }
 
 // The same decisions as classify() for many row blocks of one axis against ONE fixed position range
@@ -112,9 +130,10 @@ __host__ __device__ __forceinline__ int classify_range(const MaskDev& mk, int lo
 // block that straddles the two segments falls back to classify().
 template <bool Q_AXIS>
 struct BlockClassifier {
-  // Q_AXIS: first row that sees some / all keys; else: end of the rows seen by some / all queries;
-  // one pair per segment (scalar members: the thresholds must stay in registers)
-  int32_t some0, some1, all0, all1;
+  // Per segment, in rows of the chunk: the rows that can see / be seen by SOME row of the other side
+  // are [some_lo, some_hi), those that see / are seen by ALL of them [all_lo, all_hi).  Without a
+  // window one end of each is a segment end.  (Scalar members: the thresholds must stay in registers.)
+  int32_t some_lo0, some_hi0, all_lo0, all_hi0, some_lo1, some_hi1, all_lo1, all_hi1;
   int32_t olo, ohi, seg_len, two, empty;
 
   __host__ __device__ __forceinline__ void init(const MaskDev& mk, int olo_, int ohi_, int rows, bool other_empty) {
@@ -123,39 +142,40 @@ struct BlockClassifier {
     empty = other_empty;
     two = (Q_AXIS ? mk.q_nseg : mk.k_nseg) > 1;
     seg_len = two ? (Q_AXIS ? mk.q_seg_len : mk.k_seg_len) : rows;
-    segment(mk, 0, Q_AXIS ? mk.q_seg_pos[0] : mk.k_seg_pos[0], some0, all0);
-    segment(mk, seg_len, Q_AXIS ? mk.q_seg_pos[1] : mk.k_seg_pos[1], some1, all1);
+    segment(mk, 0, Q_AXIS ? mk.q_seg_pos[0] : mk.k_seg_pos[0], some_lo0, some_hi0, all_lo0, all_hi0);
+    segment(mk, seg_len, Q_AXIS ? mk.q_seg_pos[1] : mk.k_seg_pos[1], some_lo1, some_hi1, all_lo1, all_hi1);
   }
-  __host__ __device__ __forceinline__ void segment(const MaskDev& mk, int start, int pos0, int32_t& some, int32_t& all) const {
+  __host__ __device__ __forceinline__ void segment(const MaskDev& mk, int start, int pos0, int32_t& some_lo,
+                                                   int32_t& some_hi, int32_t& all_lo, int32_t& all_hi) const {
+    const int st = mk.pos_stride;
+    const long long w = mk.window;
     if (empty) {   // nothing on the other side: every block is empty
-      some = all = Q_AXIS ? 0x7fffffff : -1;
+      some_lo = some_hi = all_lo = all_hi = start;
     } else if (!mk.causal) {
-      some = all = Q_AXIS ? start : start + seg_len;
-    } else if (Q_AXIS) {   // row r of the segment sees key position k iff pos0 + r*stride >= k
-      some = start + rows_below(olo - pos0, mk.pos_stride);
-      all = start + rows_below(ohi - pos0, mk.pos_stride);
-    } else {               // key row r is seen from query position q iff pos0 + r*stride <= q
-      some = start + rows_upto(ohi - pos0, mk.pos_stride);
-      all = start + rows_upto(olo - pos0, mk.pos_stride);
+      some_lo = all_lo = start;
+      some_hi = all_hi = start + seg_len;
+    } else if (Q_AXIS) {
+      // query position p sees key position k iff k <= p < k + window; keys span [olo, ohi]
+      some_lo = start + rows_below((long long)olo - pos0, st, seg_len);        // first p >= olo
+      some_hi = start + rows_below((long long)ohi + w - pos0, st, seg_len);    // first p >= ohi + window
+      all_lo = start + rows_below((long long)ohi - pos0, st, seg_len);         // first p >= ohi
+      all_hi = start + rows_below((long long)olo + w - pos0, st, seg_len);     // first p >= olo + window
+    } else {
+      // key position k is seen from query position p iff p - window < k <= p; queries span [olo, ohi]
+      some_lo = start + rows_below((long long)olo - w + 1 - pos0, st, seg_len);   // first k > olo - window
+      some_hi = start + rows_upto((long long)ohi - pos0, st, seg_len);            // end of k <= ohi
+      all_lo = start + rows_below((long long)ohi - w + 1 - pos0, st, seg_len);    // first k > ohi - window
+      all_hi = start + rows_upto((long long)olo - pos0, st, seg_len);             // end of k <= olo
     }
-  }
-  // rows r >= 0 of a segment with r*stride < gap, capped at the segment length
-  __host__ __device__ __forceinline__ int rows_below(int gap, int stride) const {
-    const int n = gap <= 0 ? 0 : (gap + stride - 1) / stride;
-    return n < seg_len ? n : seg_len;
-  }
-  // rows r >= 0 of a segment with r*stride <= room, capped at the segment length
-  __host__ __device__ __forceinline__ int rows_upto(int room, int stride) const {
-    const int n = room < 0 ? 0 : room / stride + 1;
-    return n < seg_len ? n : seg_len;
   }
   // block of rows [r0, r1), r1 > r0, both inside the chunk
   __host__ __device__ __forceinline__ int operator()(const MaskDev& mk, int r0, int r1, bool ragged) const {
     if (two && r0 < seg_len && r1 > seg_len) return classify_straddle(mk, r0, r1, ragged);
     const bool second = two && r0 >= seg_len;
-    const int some_s = second ? some1 : some0, all_s = second ? all1 : all0;
-    const bool skip = Q_AXIS ? r1 <= some_s : r0 >= some_s;
-    const bool full = (Q_AXIS ? r0 >= all_s : r1 <= all_s) && !ragged;
+    const int s_lo = second ? some_lo1 : some_lo0, s_hi = second ? some_hi1 : some_hi0;
+    const int a_lo = second ? all_lo1 : all_lo0, a_hi = second ? all_hi1 : all_hi0;
+    const bool skip = r1 <= s_lo || r0 >= s_hi;
+    const bool full = r0 >= a_lo && r1 <= a_hi && !ragged;
     return skip ? TILE_SKIP : (full ? TILE_FULL : TILE_PARTIAL);
   }
   __host__ __device__ __forceinline__ int classify_straddle(const MaskDev& mk, int r0, int r1, bool ragged) const {
@@ -184,7 +204,8 @@ __device__ __forceinline__ void mask_tile(f32x16& s, const MaskDev& mk, int row0
     const int row = row0 + 8 * (v >> 2) + (v & 3);
     const bool second = row >= split;
     const int pos = (second ? pos1 : pos0) + (row - (second ? seg_len : 0)) * mk.pos_stride;
-    const bool ordered = KEYS_IN_REGS ? (lane_pos >= pos) : (pos >= lane_pos);
+    const int diff = KEYS_IN_REGS ? lane_pos - pos : pos - lane_pos;   // pos(q) - pos(k)
+    const bool ordered = (diff >= 0) & (diff < mk.window);
     const bool vis = (row < n_rows) & ((mk.causal == 0) | ordered);
     s[v] = vis ? s[v] : -INFINITY;
   }
@@ -245,13 +266,13 @@ struct TileRuns {
 };
 
 // Tiles of TILE rows along the query axis (Q_AXIS) or the key axis that can hold a pair visible to
-// the other side, in closed form: under a causal mask the rows of a query segment that see a key
-// range are the suffix with position >= `bound` (the lowest key position), the rows of a key segment
-// seen by a query range the prefix with position <= `bound` (the highest query position); a chunk
-// has at most two segments, hence at most two runs.  A tile in a run may still turn out empty for
-// a narrower row range; a tile outside the runs never holds a visible pair.
+// the other side, whose positions span [olo, ohi], in closed form: under a causal mask the rows of a
+// query segment that see some key are those with olo <= position < ohi + window, the rows of a key
+// segment seen by some query those with olo - window < position <= ohi: one stretch of rows per
+// segment, and a chunk has at most two segments, hence at most two runs.  A tile in a run may still
+// turn out empty for a narrower row range; a tile outside the runs never holds a visible pair.
 template <bool Q_AXIS, int TILE>
-__host__ __device__ __forceinline__ TileRuns visible_tiles(const MaskDev& mk, int bound, int rows) {
+__host__ __device__ __forceinline__ TileRuns visible_tiles(const MaskDev& mk, int olo, int ohi, int rows) {
   TileRuns tr{{0, 0}, {0, 0}};
   if (rows <= 0) return tr;
   if (!mk.causal) {
@@ -260,20 +281,17 @@ __host__ __device__ __forceinline__ TileRuns visible_tiles(const MaskDev& mk, in
   }
   const int nseg = Q_AXIS ? mk.q_nseg : mk.k_nseg;
   const int seg_len = nseg > 1 ? (Q_AXIS ? mk.q_seg_len : mk.k_seg_len) : rows;
+  const long long w = mk.window;
   int n = 0, prev_end = 0;
 #pragma unroll
   for (int s = 0; s < 2; ++s) {   // constant indices only: the mask must stay in registers
     if (s >= nseg) break;
     const int pos0 = Q_AXIS ? mk.q_seg_pos[s] : mk.k_seg_pos[s];
-    int r0 = 0, r1 = seg_len;   // visible rows of the segment, counted from its start
-    if (Q_AXIS) {
-      const int need = bound - pos0;
-      r0 = need <= 0 ? 0 : (need + mk.pos_stride - 1) / mk.pos_stride;
-    } else {
-      const int room = bound - pos0;
-      const int cnt = room < 0 ? 0 : room / mk.pos_stride + 1;
-      r1 = cnt < seg_len ? cnt : seg_len;
-    }
+    // visible rows of the segment, counted from its start
+    const int r0 = Q_AXIS ? rows_below((long long)olo - pos0, mk.pos_stride, seg_len)
+                          : rows_below((long long)olo - w + 1 - pos0, mk.pos_stride, seg_len);
+    const int r1 = Q_AXIS ? rows_below((long long)ohi + w - pos0, mk.pos_stride, seg_len)
+                          : rows_upto((long long)ohi - pos0, mk.pos_stride, seg_len);
     if (r0 >= r1) continue;
     int a = (s * seg_len + r0) / TILE;
     const int b = (s * seg_len + r1 + TILE - 1) / TILE;
@@ -362,11 +380,11 @@ struct KvWalk {
   const char *k_base, *v_base, *k_tile, *v_tile;   // row 0 of the head; first row of the cursor's tile
   int64_t k_row, v_row;   // bytes per key row
 
-  // q_hi: highest position among the query rows of the work-group
+  // [q_lo, q_hi]: positions spanned by the query rows of the work-group
   __device__ __forceinline__ void init(const MaskDev& mk, const TensorDev& k, const TensorDev& v, int b, int hk, int sk_,
-                                       int q_hi, int tid) {
+                                       int q_lo, int q_hi, int tid) {
     sk = sk_;
-    runs = visible_tiles<false, BK>(mk, q_hi, sk);
+    runs = visible_tiles<false, BK>(mk, q_lo, q_hi, sk);
     n_tiles = runs.total();
     run = 0;
     left = runs.len[0];

@@ -67,7 +67,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
   auto tile_class = [&](int k0_) { return k_class(mk, k0_, min(k0_ + BK, sk), k0_ + BK > sk); };   // wave-uniform
 
   KvWalk<D, BK, NT> walk;
-  walk.init(mk, p.k, p.v, b, hk, sk, qhi_blk, tid);
+  walk.init(mk, p.k, p.v, b, hk, sk, qlo_blk, qhi_blk, tid);
   wait_global_loads();
   int k0 = 0, cls = TILE_SKIP;   // first key row and class of the tile in LDS
   if (walk.n_tiles > 0) {

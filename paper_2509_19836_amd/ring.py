@@ -13,31 +13,35 @@ def ring_order(i, G):
     return [(i - t) % G for t in range(G)]
 
 
-def fill_mask(kind, i, j, G, N):
-    """kind: "full" / "causal" (contiguous split), "zigzag", "striped"."""
+def fill_mask(kind, i, j, G, N, window=0):
+    """kind: "full" / "causal" (contiguous split), "zigzag", "striped"; window > 0: sliding-window
+    attention over the causal kinds (each token sees itself and the window - 1 positions before it)."""
     if kind == "full":
-        return lib.burst_attn_fill_contiguous_mask(i, j, G, N, False)
-    if kind == "causal":
-        return lib.burst_attn_fill_contiguous_mask(i, j, G, N, True)
-    if kind == "zigzag":
-        return lib.burst_attn_fill_zigzag_mask(i, j, G, N, True)
-    if kind == "striped":
-        return lib.burst_attn_fill_striped_mask(i, j, G, N, True)
-    raise ValueError(kind)
+        m = lib.burst_attn_fill_contiguous_mask(i, j, G, N, False)
+    elif kind == "causal":
+        m = lib.burst_attn_fill_contiguous_mask(i, j, G, N, True)
+    elif kind == "zigzag":
+        m = lib.burst_attn_fill_zigzag_mask(i, j, G, N, True)
+    elif kind == "striped":
+        m = lib.burst_attn_fill_striped_mask(i, j, G, N, True)
+    else:
+        raise ValueError(kind)
+    m.window = window
+    return m
 
 
-def ring_forward(i, G, N, kind, scale, q_i, k_shards, v_shards, o_acc, lse_acc, stream=None):
+def ring_forward(i, G, N, kind, scale, q_i, k_shards, v_shards, o_acc, lse_acc, stream=None, window=0):
     """o_acc / lse_acc must hold (0, -inf) on entry; they hold (O_i, Lse_i) on return."""
     B, n, Hq, d = q_i.shape
     for j in ring_order(i, G):
         k_j, v_j = k_shards[j], v_shards[j]
         shp = lib.shape(B, Hq, k_j.shape[2], d, n, k_j.shape[1], scale)
-        lib.burst_attn_step_fwd(shp, fill_mask(kind, i, j, G, N), q_i, k_j, v_j,
+        lib.burst_attn_step_fwd(shp, fill_mask(kind, i, j, G, N, window), q_i, k_j, v_j,
                                 o_acc=o_acc, lse_acc=lse_acc, stream=stream)
 
 
 def ring_backward(i, G, N, kind, scale, q_i, do_i, o_i, lse_i, d_i, k_shards, v_shards, dq_i, dk_shards,
-                  dv_shards, stream=None):
+                  dv_shards, stream=None, window=0):
     """D_i once, then one backward step per shard; dq_i, dk_shards[j], dv_shards[j] are fp32
     accumulators ("+=")."""
     B, n, Hq, d = q_i.shape
@@ -47,6 +51,6 @@ def ring_backward(i, G, N, kind, scale, q_i, do_i, o_i, lse_i, d_i, k_shards, v_
     for j in ring_order(i, G):
         k_j, v_j = k_shards[j], v_shards[j]
         shp = lib.shape(B, Hq, k_j.shape[2], d, n, k_j.shape[1], scale)
-        lib.burst_attn_step_bwd(shp, fill_mask(kind, i, j, G, N), q_i, k_j, v_j, do_i, lse_i, d_i,
+        lib.burst_attn_step_bwd(shp, fill_mask(kind, i, j, G, N, window), q_i, k_j, v_j, do_i, lse_i, d_i,
                                 dq=dq_i, dk=dk_shards[j], dv=dv_shards[j], accumulate_flags=flags,
                                 stream=stream)

@@ -18,17 +18,20 @@ def mask_positions(mask, side):
                            for s in range(nseg)])
 
 
-def fill_mask(lib, kind, i, j, G, N):
-    """kind: full | causal (contiguous split) | zigzag | striped | zigzag_full."""
+def fill_mask(lib, kind, i, j, G, N, window=0):
+    """kind: full | causal (contiguous split) | zigzag | striped; window > 0 adds a sliding window."""
     if kind == "full":
-        return lib.burst_attn_fill_contiguous_mask(i, j, G, N, False)
-    if kind == "causal":
-        return lib.burst_attn_fill_contiguous_mask(i, j, G, N, True)
-    if kind == "zigzag":
-        return lib.burst_attn_fill_zigzag_mask(i, j, G, N, True)
-    if kind == "striped":
-        return lib.burst_attn_fill_striped_mask(i, j, G, N, True)
-    raise ValueError(kind)
+        m = lib.burst_attn_fill_contiguous_mask(i, j, G, N, False)
+    elif kind == "causal":
+        m = lib.burst_attn_fill_contiguous_mask(i, j, G, N, True)
+    elif kind == "zigzag":
+        m = lib.burst_attn_fill_zigzag_mask(i, j, G, N, True)
+    elif kind == "striped":
+        m = lib.burst_attn_fill_striped_mask(i, j, G, N, True)
+    else:
+        raise ValueError(kind)
+    m.window = window
+    return m
 
 
 def oracle_positions(oc, kind, i, G, N):

@@ -16,7 +16,7 @@ def _torch():
     return torch
 
 
-def full_ring_case(lib, w, cfg_index, kind, travel="kv"):
+def full_ring_case(lib, w, cfg_index, kind, travel="kv", window=0):
     """Whole simulated ring, every device: forward (fused merge), D, then all G*G backward steps.
     travel = "kv": Alg. 1 order (Q_i stays, dQ_i accumulates locally, dK_j/dV_j of the visiting
     chunk accumulate across devices); travel = "q": Alg. 2 order (K_i, V_i, dK_i, dV_i stay, the
@@ -26,7 +26,7 @@ def full_ring_case(lib, w, cfg_index, kind, travel="kv"):
     T = wl.host_tensors(w, cfg_index)
     Q, K, V, dO = (hp.widen(T[n][1]) for n in ("q", "k", "v", "do"))
     causal = kind != "full"
-    vis_glob = oc.visibility(np.arange(N), np.arange(N), causal)
+    vis_glob = oc.visibility(np.arange(N), np.arange(N), causal, window)
     O_ref, lse_ref = oc.mha_attention_fwd(Q, K, V, w.scale, vis_glob)
     dQ_ref, dK_ref, dV_ref = oc.mha_attention_bwd(Q, K, V, dO, w.scale, vis_glob)
     D_ref = oc.mha_preprocess_bwd(dO, O_ref)
@@ -42,7 +42,7 @@ def full_ring_case(lib, w, cfg_index, kind, travel="kv"):
         lse_acc = torch.full((w.batch, w.q_heads, n), -float("inf"), **f32)
         for j in oc.ring_order(i, G):
             shp = lib.shape(w.batch, w.q_heads, w.kv_heads, w.head_dim, n, n, w.scale)
-            lib.burst_attn_step_fwd(shp, hp.fill_mask(lib, kind, i, j, G, N), sh[i]["q"], sh[j]["k"], sh[j]["v"],
+            lib.burst_attn_step_fwd(shp, hp.fill_mask(lib, kind, i, j, G, N, window), sh[i]["q"], sh[j]["k"], sh[j]["v"],
                                     o_acc=o_acc, lse_acc=lse_acc)
         d_i = torch.empty(w.batch, w.q_heads, n, **f32)
         lib.burst_attn_preprocess_bwd(lib.shape(w.batch, w.q_heads, w.kv_heads, w.head_dim, n, n, w.scale),
@@ -61,7 +61,7 @@ def full_ring_case(lib, w, cfg_index, kind, travel="kv"):
         for t in range(G):
             # (i, j) = (query device, key device)
             i, j = (a, (a - t) % G) if travel == "kv" else ((a - t) % G, a)
-            lib.burst_attn_step_bwd(shp, hp.fill_mask(lib, kind, i, j, G, N), sh[i]["q"], sh[j]["k"], sh[j]["v"],
+            lib.burst_attn_step_bwd(shp, hp.fill_mask(lib, kind, i, j, G, N, window), sh[i]["q"], sh[j]["k"], sh[j]["v"],
                                     sh[i]["do"], lse[i], Dv[i], dq=dq[i], dk=dk[j], dv=dv[j],
                                     accumulate_flags=ALL)
     torch.cuda.synchronize()
@@ -99,6 +99,17 @@ def test_config4_scaled_full_head_scales_backward(lib):
 
 def test_striped_backward(lib):
     full_ring_case(lib, wl.Workload("striped", 1, 2, 2, 128, 320, 4, "striped"), 6, "striped")
+
+
+@pytest.mark.parametrize("kind,window", [("causal", 1), ("causal", 100), ("causal", 300), ("zigzag", 64), ("zigzag", 200),
+                                         ("striped", 37), ("striped", 500)])
+def test_sliding_window_ring_backward(lib, kind, window):
+    full_ring_case(lib, wl.WORKLOADS[1], 1, kind, window=window)
+
+
+def test_sliding_window_scaled_config2_d128_backward(lib):
+    w = wl.Workload("zigzag_window_d128", 1, 4, 4, 128, 512, 4, "zigzag")
+    full_ring_case(lib, w, 2, "zigzag", window=w.seq // 4)
 
 
 @pytest.mark.parametrize("d", [64, 128])

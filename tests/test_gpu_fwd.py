@@ -16,7 +16,7 @@ def _torch():
     return torch
 
 
-def ring_case(lib, w, cfg_index, kind, devices, o_part_dtype="f32", reverse=False):
+def ring_case(lib, w, cfg_index, kind, devices, o_part_dtype="f32", reverse=False, window=0):
     """All ring steps of the given devices: per-step partials vs oracle.step_fwd, fused running state
     and the standalone merge vs the unsharded oracle."""
     torch = _torch()
@@ -24,7 +24,7 @@ def ring_case(lib, w, cfg_index, kind, devices, o_part_dtype="f32", reverse=Fals
     T = wl.host_tensors(w, cfg_index)
     Q, K, V = (hp.widen(T[n][1]) for n in ("q", "k", "v"))
     causal = kind != "full"
-    vis_glob = oc.visibility(np.arange(N), np.arange(N), causal)
+    vis_glob = oc.visibility(np.arange(N), np.arange(N), causal, window)
     O_ref, lse_ref = oc.mha_attention_fwd(Q, K, V, w.scale, vis_glob)
     qd, kd, vd = (hp.dev_bf16(T[n][1]) for n in ("q", "k", "v"))
     worst = {"o_part": 0.0, "lse_part": 0.0, "o_fused": 0.0, "lse_fused": 0.0, "o_merge": 0.0, "lse_merge": 0.0}
@@ -38,7 +38,7 @@ def ring_case(lib, w, cfg_index, kind, devices, o_part_dtype="f32", reverse=Fals
         lse_acc = torch.full((w.batch, w.q_heads, n), -float("inf"), device="cuda", dtype=torch.float32)
         o_acc2, lse_acc2 = o_acc.clone(), lse_acc.clone()
         for j in oc.ring_order(i, G, reverse):
-            mask = hp.fill_mask(lib, kind, i, j, G, N)
+            mask = hp.fill_mask(lib, kind, i, j, G, N, window)
             krows = hp.mask_positions(mask, "k")
             kidx = torch.from_numpy(krows).cuda()
             k_j, v_j = kd[:, kidx].contiguous(), vd[:, kidx].contiguous()
@@ -50,7 +50,7 @@ def ring_case(lib, w, cfg_index, kind, devices, o_part_dtype="f32", reverse=Fals
             lib.burst_attn_step_fwd(shp, mask, q_i, k_j, v_j, o_acc=o_acc, lse_acc=lse_acc)
             lib.burst_attn_lse_merge(shp, o_acc2, lse_acc2, o_part, lse_part)
             torch.cuda.synchronize()
-            vis = oc.visibility(qrows, krows, causal)
+            vis = oc.visibility(qrows, krows, causal, window)
             O_s, lse_s = oc.mha_step_fwd(Q[:, qrows], K[:, krows], V[:, krows], w.scale, vis)
             worst["o_part"] = max(worst["o_part"], hp.rel_err(o_part.float().cpu().numpy(), O_s))
             worst["lse_part"] = max(worst["lse_part"], hp.lse_err(lse_part.cpu().numpy(), lse_s))
@@ -58,7 +58,7 @@ def ring_case(lib, w, cfg_index, kind, devices, o_part_dtype="f32", reverse=Fals
         worst["lse_fused"] = max(worst["lse_fused"], hp.lse_err(lse_acc.cpu().numpy(), lse_ref[:, :, qrows]))
         worst["o_merge"] = max(worst["o_merge"], hp.rel_err(o_acc2.cpu().numpy(), O_ref[:, qrows]))
         worst["lse_merge"] = max(worst["lse_merge"], hp.lse_err(lse_acc2.cpu().numpy(), lse_ref[:, :, qrows]))
-    print(f"\n[{w.name} {kind}] worst errors: {worst}", flush=True)
+    print(f"\n[{w.name} {kind} window {window}] worst errors: {worst}", flush=True)
     for kname, val in worst.items():
         assert val <= (hp.LSE_TOL if kname.startswith("lse") else hp.REL_TOL), (kname, val)
 
@@ -91,6 +91,19 @@ def test_config4_scaled_full_head_scales(lib):
 def test_striped_partition(lib):
     w = wl.Workload("striped", 1, 2, 2, 128, 320, 4, "striped")
     ring_case(lib, w, 6, "striped", devices=[0, 3])
+
+
+@pytest.mark.parametrize("kind,window", [("causal", 1), ("causal", 100), ("causal", 300), ("zigzag", 64), ("zigzag", 200),
+                                         ("striped", 37), ("striped", 500)])
+def test_sliding_window_ring(lib, kind, window):
+    """Sliding-window attention over the three partitions: every step's partial (some steps see
+    nothing at all), the fused running state and the standalone merge, against the windowed oracle."""
+    ring_case(lib, wl.WORKLOADS[1], 1, kind, range(4), window=window)
+
+
+def test_sliding_window_scaled_config2_d128(lib):
+    w = wl.Workload("zigzag_window_d128", 1, 4, 4, 128, 512, 4, "zigzag")
+    ring_case(lib, w, 2, "zigzag", [0, 1, 3], window=w.seq // 4)
 
 
 @pytest.mark.parametrize("d", [64, 128])
