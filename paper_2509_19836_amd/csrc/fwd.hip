@@ -1,9 +1,9 @@
 // Forward step kernel: O_ij, Lse_cur of a query chunk against one key/value chunk (Eq. 5-6),
 // optionally folded into the running (O_i, Lse_i) in the epilogue (forward algorithm lines 6-9).
 //
-// One work-group = 4 waves = 128 query rows of one (batch, head); wave w owns rows [32w, 32w+32).
-// The key/value chunk streams through LDS in tiles of 64 rows, double buffered, one barrier per
-// tile.  Everything is computed transposed so that a lane always owns one query row:
+// One work-group = 8 waves = 256 query rows of one (batch, head); wave w owns rows [32w, 32w+32),
+// two waves per SIMD.  The key/value chunk streams through LDS in tiles of 64 rows, double buffered,
+// one barrier per tile.  Everything is computed transposed so that a lane always owns one query row:
 //   S^T = K Q^T   (A = K rows from LDS, B = Q held in registers),
 //   P^T = exp2(..) in the accumulator registers, packed to bf16 and fed straight back as the
 //   B operand of  O^T = V^T P^T  (A = V columns via transposing LDS reads).
