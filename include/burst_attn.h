@@ -17,8 +17,8 @@
  *   - Layouts: 4-D tensors are [batch, seq, heads, head_dim] with head_dim contiguous and the
  *     other strides given in ELEMENTS; row vectors (lse, D) are fp32 [batch, heads, seq] with seq
  *     contiguous and strides in elements.  4-D tensor pointers must be 16-byte aligned and their
- *     strides multiples of 8 elements (bf16) or 4 elements (fp32); row vectors need only their
- *     natural 4-byte alignment.
+ *     strides multiples of 8 elements (bf16) or 4 elements (fp32), stride_s at most 2^24 elements
+ *     (BURST_ERR_UNSUPPORTED beyond); row vectors need only their natural 4-byte alignment.
  *   - q, k, v, dO are bfloat16.  Accumulation, softmax, lse and D are fp32.
  *   - head_dim is 64 or 128; q_heads must be a multiple of kv_heads; query head h uses key/value
  *     head h / (q_heads / kv_heads).  sq and sk may be any non-negative number (ragged tails and

@@ -12,6 +12,19 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffast-math", "
          "-Wno-unused-command-line-argument"]
 
 
+def check_resources(remarks, src):
+    """The kernels are written to live in registers: a kernel that spills vector registers or touches
+    scratch memory (a dynamically indexed struct does that silently) runs several times slower, so
+    the build refuses it.  `remarks` is hipcc's -Rpass-analysis=kernel-resource-usage output."""
+    name = None
+    for line in remarks.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split("[")[0].strip()
+        for what in ("ScratchSize [bytes/lane]:", "VGPRs Spill:"):
+            if what in line and int(line.split(what)[1].split("[")[0]) != 0:
+                raise RuntimeError(f"{src}: kernel {name} has {line.split('remark:')[1].strip()}")
+
+
 def build(verbose=False, extra_flags=(), out_path=None, tag=""):
     """Compile every source to an object (in parallel) and link the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -20,7 +33,7 @@ def build(verbose=False, extra_flags=(), out_path=None, tag=""):
     procs = []
     for src in SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, "-Rpass-analysis=kernel-resource-usage", *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, obj, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -30,6 +43,7 @@ def build(verbose=False, extra_flags=(), out_path=None, tag=""):
         out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
         if pr.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
+        check_resources(out, src)
         if verbose and out.strip():
             print(out)
         objs.append(obj)

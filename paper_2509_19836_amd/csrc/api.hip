@@ -20,6 +20,7 @@ int hip_fail(hipError_t e) {
 
 constexpr int64_t kMaxRows = (int64_t)1 << 30;
 constexpr int64_t kMaxPos = ((int64_t)1 << 31) - 1;
+constexpr int64_t kMaxRowStride = (int64_t)1 << 24;   // elements between consecutive sequence rows
 
 int check_shape(const burst_shape_t* s) {
   if (!s) return BURST_ERR_INVALID_ARG;
@@ -39,6 +40,7 @@ int check_tensor(const burst_tensor_t* t, int want_dtype_mask /* bit0 bf16 ok, b
   const int64_t unit = (t->dtype == BURST_BF16) ? 8 : 4;
   if (t->stride_b % unit || t->stride_s % unit || t->stride_h % unit) return BURST_ERR_INVALID_ARG;
   if (t->stride_b < 0 || t->stride_s < 0 || t->stride_h < 0) return BURST_ERR_INVALID_ARG;
+  if (t->stride_s > kMaxRowStride) return BURST_ERR_UNSUPPORTED;   // the tile stagers keep 32-bit byte offsets inside a tile
   out->ptr = t->ptr;
   out->sb = t->stride_b;
   out->ss = t->stride_s;

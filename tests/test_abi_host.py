@@ -122,6 +122,9 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert fwd(mask=lib.burst_mask_t(1, 1, 1, 0, (0, 0), (0, 0), 64, 64, 0)) == INV      # stride
     assert fwd(mask=lib.burst_mask_t(1, 1, 1, 0, (-5, 0), (0, 0), 64, 64, 1)) == INV     # negative position
     assert fwd(mask=lib.burst_mask_t(1, 1, 1, 0, (1 << 31, 0), (0, 0), 64, 64, 1)) == UNS  # position range
+    assert fwd(mask=lib.burst_mask_t(1, 1, 1, 0, (0, 0), (0, 0), 64, 64, 1, -3)) == INV    # negative window
+    assert fwd(mask=lib.burst_mask_t(0, 1, 1, 0, (0, 0), (0, 0), 64, 64, 1, 16)) == INV    # window without causal
+    assert fwd(k=_fake_tensor(lib, strides=(1 << 40, (1 << 24) + 8, 128))) == UNS          # row stride beyond 2^24
 
     def bwd(dq=tf32, dk=tf32, dv=tf32, flags=0, lse=rv, d=rv, d_o=t):
         ref = lambda x: None if x is None else r(x)
