@@ -170,13 +170,16 @@ struct BlockClassifier {
   }
   // block of rows [r0, r1), r1 > r0, both inside the chunk
   __host__ __device__ __forceinline__ int operator()(const MaskDev& mk, int r0, int r1, bool ragged) const {
-    if (two && r0 < seg_len && r1 > seg_len) return classify_straddle(mk, r0, r1, ragged);
-    const bool second = two && r0 >= seg_len;
+    // bitwise logic and selects only: this runs once per tile in every wave, and short-circuit
+    // operators compile to a chain of scalar branches
+    if ((two != 0) & (r0 < seg_len) & (r1 > seg_len)) return classify_straddle(mk, r0, r1, ragged);   // rare
+    const bool second = (two != 0) & (r0 >= seg_len);
     const int s_lo = second ? some_lo1 : some_lo0, s_hi = second ? some_hi1 : some_hi0;
     const int a_lo = second ? all_lo1 : all_lo0, a_hi = second ? all_hi1 : all_hi0;
-    const bool skip = r1 <= s_lo || r0 >= s_hi;
-    const bool full = r0 >= a_lo && r1 <= a_hi && !ragged;
-    return skip ? TILE_SKIP : (full ? TILE_FULL : TILE_PARTIAL);
+    const bool skip = (r1 <= s_lo) | (r0 >= s_hi);
+    const bool full = (r0 >= a_lo) & (r1 <= a_hi) & !ragged;
+    const int cls = full ? TILE_FULL : TILE_PARTIAL;
+    return skip ? TILE_SKIP : cls;
   }
   __host__ __device__ __forceinline__ int classify_straddle(const MaskDev& mk, int r0, int r1, bool ragged) const {
     if (empty) return TILE_SKIP;
