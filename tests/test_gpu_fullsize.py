@@ -20,20 +20,23 @@ def _sample_rows(n, seg, rng, extra=24):
     return np.array(sorted(rows), dtype=np.int64)
 
 
-@pytest.mark.parametrize("shard_j", [3, 1, 5])
-def test_config2_step_sampled_rows(lib, shard_j):
+def _step_sampled(lib, B, n, Hq, Hkv, d, mask, scale, seed, head_scale=False, batch_index=0, heads=None):
+    """One forward and one backward step at the given size; whole sampled query rows and whole sampled
+    key rows of a few heads against the oracle."""
     import torch
-    w = wl.WORKLOADS[2]
-    G, N, i = w.shards, w.seq, 3
-    B, n, Hq, Hkv, d = w.batch, w.shard_tokens, w.q_heads, w.kv_heads, w.head_dim
     gen = torch.Generator(device="cuda")
-    gen.manual_seed(wl.BASE_SEED + 200 + shard_j)
-    draw = lambda heads: torch.randn(B, n, heads, d, device="cuda", generator=gen).to(torch.bfloat16)
+    gen.manual_seed(seed)
+
+    def draw(nheads):
+        x = torch.randn(B, n, nheads, d, device="cuda", generator=gen)
+        if head_scale:
+            x = x * torch.empty(B, 1, nheads, 1, device="cuda").uniform_(0.5, 2.0, generator=gen)
+        return x.to(torch.bfloat16)
+
     q, do, k, v = draw(Hq), draw(Hq), draw(Hkv), draw(Hkv)
-    mask = lib.burst_attn_fill_zigzag_mask(i, shard_j, G, N)
+    causal = mask.mode == lib.BURST_MASK_CAUSAL
     qpos, kpos = hp.mask_positions(mask, "q"), hp.mask_positions(mask, "k")
-    assert (qpos == oc.zigzag_positions(i, G, N)).all() and (kpos == oc.zigzag_positions(shard_j, G, N)).all()
-    shp = lib.shape(B, Hq, Hkv, d, n, n, w.scale)
+    shp = lib.shape(B, Hq, Hkv, d, n, n, scale)
     f32 = dict(device="cuda", dtype=torch.float32)
     o_part = torch.empty(B, n, Hq, d, **f32)
     lse_part = torch.empty(B, Hq, n, **f32)
@@ -48,34 +51,66 @@ def test_config2_step_sampled_rows(lib, shard_j):
     torch.cuda.synchronize()
     assert torch.isfinite(dq).all() and torch.isfinite(dk).all() and torch.isfinite(dv).all()
 
-    rng = np.random.Generator(np.random.PCG64(wl.BASE_SEED + 300 + shard_j))
+    rng = np.random.Generator(np.random.PCG64(seed + 100))
     rows = _sample_rows(n, n // 2, rng)
     cols = _sample_rows(n, n // 2, rng)
     to64 = lambda t: t.float().cpu().numpy().astype(np.float64)
-    for head in (0, Hq - 1):
-        Qh, dOh, Kh, Vh = to64(q[0, :, head]), to64(do[0, :, head]), to64(k[0, :, head]), to64(v[0, :, head])
-        lse_h, d_h = to64(lse_in[0, head]), to64(d_in[0, head])
+    bi, group = batch_index, Hq // Hkv
+    for head in heads or (0, Hq - 1):
+        kvh = head // group
+        Qh, dOh, Kh, Vh = to64(q[bi, :, head]), to64(do[bi, :, head]), to64(k[bi, :, kvh]), to64(v[bi, :, kvh])
+        lse_h, d_h = to64(lse_in[bi, head]), to64(d_in[bi, head])
         # whole query rows
-        vis_r = oc.visibility(qpos[rows], kpos, True)
-        O_ref, lse_ref = oc.step_fwd(Qh[rows], Kh, Vh, w.scale, vis_r)
-        o_scale = np.abs(to64(o_part[0, :, head])).max()
-        assert np.abs(to64(o_part[0, :, head])[rows] - O_ref).max() <= hp.REL_TOL * o_scale
-        assert hp.lse_err(to64(lse_part[0, head])[rows], lse_ref) <= hp.LSE_TOL
-        dQ_ref, _, _ = oc.step_bwd(Qh[rows], Kh, Vh, dOh[rows], lse_h[rows], d_h[rows], w.scale, vis_r)
-        dq_scale = np.abs(to64(dq[0, :, head])).max()
-        assert np.abs(to64(dq[0, :, head])[rows] - dQ_ref).max() <= hp.REL_TOL * dq_scale
-        # whole key rows
-        vis_c = oc.visibility(qpos, kpos[cols], True)
-        _, dK_ref, dV_ref = oc.step_bwd(Qh, Kh[cols], Vh[cols], dOh, lse_h, d_h, w.scale, vis_c)
-        dk_scale, dv_scale = np.abs(to64(dk[0, :, head])).max(), np.abs(to64(dv[0, :, head])).max()
-        assert np.abs(to64(dk[0, :, head])[cols] - dK_ref).max() <= hp.REL_TOL * dk_scale
-        assert np.abs(to64(dv[0, :, head])[cols] - dV_ref).max() <= hp.REL_TOL * dv_scale
-        # rows / columns the mask empties entirely must be exactly (0, -inf) / 0
+        vis_r = oc.visibility(qpos[rows], kpos, causal, mask.window)
+        O_ref, lse_ref = oc.step_fwd(Qh[rows], Kh, Vh, scale, vis_r)
+        o_scale = np.abs(to64(o_part[bi, :, head])).max()
+        assert np.abs(to64(o_part[bi, :, head])[rows] - O_ref).max() <= hp.REL_TOL * o_scale
+        assert hp.lse_err(to64(lse_part[bi, head])[rows], lse_ref) <= hp.LSE_TOL
+        dQ_ref, _, _ = oc.step_bwd(Qh[rows], Kh, Vh, dOh[rows], lse_h[rows], d_h[rows], scale, vis_r)
+        dq_scale = np.abs(to64(dq[bi, :, head])).max()
+        assert np.abs(to64(dq[bi, :, head])[rows] - dQ_ref).max() <= hp.REL_TOL * dq_scale
+        # rows the mask empties entirely must be exactly (0, -inf) / 0
         dead_r = ~vis_r.any(axis=1)
-        assert (to64(o_part[0, :, head])[rows][dead_r] == 0).all()
-        assert (to64(dq[0, :, head])[rows][dead_r] == 0).all()
-        dead_c = ~vis_c.any(axis=0)
-        assert (to64(dk[0, :, head])[cols][dead_c] == 0).all() and (to64(dv[0, :, head])[cols][dead_c] == 0).all()
+        assert (to64(o_part[bi, :, head])[rows][dead_r] == 0).all()
+        assert (to64(dq[bi, :, head])[rows][dead_r] == 0).all()
+        if group == 1:   # whole key rows (with grouped heads dK / dV sum over the group: tested separately)
+            vis_c = oc.visibility(qpos, kpos[cols], causal, mask.window)
+            _, dK_ref, dV_ref = oc.step_bwd(Qh, Kh[cols], Vh[cols], dOh, lse_h, d_h, scale, vis_c)
+            dk_scale, dv_scale = np.abs(to64(dk[bi, :, head])).max(), np.abs(to64(dv[bi, :, head])).max()
+            assert np.abs(to64(dk[bi, :, head])[cols] - dK_ref).max() <= hp.REL_TOL * dk_scale
+            assert np.abs(to64(dv[bi, :, head])[cols] - dV_ref).max() <= hp.REL_TOL * dv_scale
+            dead_c = ~vis_c.any(axis=0)
+            assert (to64(dk[bi, :, head])[cols][dead_c] == 0).all() and (to64(dv[bi, :, head])[cols][dead_c] == 0).all()
+
+
+@pytest.mark.parametrize("shard_j", [3, 1, 5])
+def test_config2_step_sampled_rows(lib, shard_j):
+    w = wl.WORKLOADS[2]
+    G, N, i = w.shards, w.seq, 3
+    mask = lib.burst_attn_fill_zigzag_mask(i, shard_j, G, N)
+    assert (hp.mask_positions(mask, "q") == oc.zigzag_positions(i, G, N)).all()
+    assert (hp.mask_positions(mask, "k") == oc.zigzag_positions(shard_j, G, N)).all()
+    _step_sampled(lib, w.batch, w.shard_tokens, w.q_heads, w.kv_heads, w.head_dim, mask, w.scale,
+                  wl.BASE_SEED + 200 + shard_j)
+
+
+@pytest.mark.parametrize("shard_j", [3, 2, 0])
+def test_config2_striped_sliding_window_sampled_rows(lib, shard_j):
+    """Config 2's shapes with the striped split and a 32768-token window (the sparse-attention
+    benchmark row): shard 0 lies ahead of device 3 inside the stripe, shard 3 is its own."""
+    w = wl.WORKLOADS[2]
+    mask = lib.burst_attn_fill_striped_mask(3, shard_j, w.shards, w.seq)
+    mask.window = 32768
+    _step_sampled(lib, w.batch, w.shard_tokens, w.q_heads, w.kv_heads, w.head_dim, mask, w.scale,
+                  wl.BASE_SEED + 400 + shard_j, heads=(7,))
+
+
+def test_config4_full_mask_head_scales_sampled_rows(lib):
+    """Config 4's launch configuration: batch 2, 65536-row chunks, full mask, per-head value scales."""
+    w = wl.WORKLOADS[4]
+    mask = lib.burst_attn_fill_contiguous_mask(1, 2, w.shards, w.seq, False)
+    _step_sampled(lib, w.batch, w.shard_tokens, w.q_heads, w.kv_heads, w.head_dim, mask, w.scale,
+                  wl.BASE_SEED + 500, head_scale=True, batch_index=1, heads=(13,))
 
 
 def test_gqa_full_size_heads_group_reduction(lib):
