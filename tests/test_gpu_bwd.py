@@ -107,6 +107,13 @@ def test_sliding_window_ring_backward(lib, kind, window):
     full_ring_case(lib, wl.WORKLOADS[1], 1, kind, window=window)
 
 
+@pytest.mark.parametrize("d,window", [(64, 0), (128, 0), (128, 90)])
+def test_zigzag_pieces_that_are_not_tile_multiples_backward(lib, d, window):
+    for piece, G in ((100, 2), (150, 3)):
+        w = wl.Workload(f"zigzag_piece{piece}", 1, 2, 2, d, 2 * piece, G, "zigzag")
+        full_ring_case(lib, w, 6, "zigzag", window=window)
+
+
 def test_sliding_window_scaled_config2_d128_backward(lib):
     w = wl.Workload("zigzag_window_d128", 1, 4, 4, 128, 512, 4, "zigzag")
     full_ring_case(lib, w, 2, "zigzag", window=w.seq // 4)

@@ -101,6 +101,15 @@ def test_sliding_window_ring(lib, kind, window):
     ring_case(lib, wl.WORKLOADS[1], 1, kind, range(4), window=window)
 
 
+@pytest.mark.parametrize("d,window", [(64, 0), (128, 0), (128, 90)])
+def test_zigzag_pieces_that_are_not_tile_multiples(lib, d, window):
+    """Zigzag pieces of 100 and 150 rows: LDS tiles straddle the seam between the front and the back
+    piece of a chunk, the last tile is ragged, and the tile runs of the two pieces touch."""
+    for piece, G in ((100, 2), (150, 3)):
+        w = wl.Workload(f"zigzag_piece{piece}", 1, 2, 2, d, 2 * piece, G, "zigzag")
+        ring_case(lib, w, 6, "zigzag", range(G), window=window)
+
+
 def test_sliding_window_scaled_config2_d128(lib):
     w = wl.Workload("zigzag_window_d128", 1, 4, 4, 128, 512, 4, "zigzag")
     ring_case(lib, w, 2, "zigzag", [0, 1, 3], window=w.seq // 4)
