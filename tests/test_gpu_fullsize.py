@@ -113,6 +113,23 @@ def test_config4_full_mask_head_scales_sampled_rows(lib):
                   wl.BASE_SEED + 500, head_scale=True, batch_index=1, heads=(13,))
 
 
+def test_config3_gqa_launch_shape_sampled_rows(lib):
+    """Config 3's launch configuration (64 query heads on 8 KV heads, 32768-row chunks): sampled query
+    rows of two heads of different groups (the group sum of dK / dV is checked at a smaller size below)."""
+    w = wl.WORKLOADS[3]
+    mask = lib.burst_attn_fill_zigzag_mask(3, 5, w.shards, w.seq)
+    _step_sampled(lib, w.batch, w.shard_tokens, w.q_heads, w.kv_heads, w.head_dim, mask, w.scale,
+                  wl.BASE_SEED + 600, heads=(9, 62))
+
+
+def test_config5_million_token_launch_shape_sampled_rows(lib):
+    """Config 5's launch configuration: 131072-row chunks of a 1M-token sequence, own-shard step."""
+    w = wl.WORKLOADS[5]
+    mask = lib.burst_attn_fill_zigzag_mask(3, 3, w.shards, w.seq)
+    _step_sampled(lib, w.batch, w.shard_tokens, w.q_heads, w.kv_heads, w.head_dim, mask, w.scale,
+                  wl.BASE_SEED + 700, heads=(21,))
+
+
 def test_gqa_full_size_heads_group_reduction(lib):
     """Config 3's grouping (64 query heads on 8 KV heads, head_dim 128) at a 4096-row shard: dK / dV of
     one KV head against the oracle summed over its 8 query heads, on sampled key rows."""
