@@ -78,6 +78,22 @@ def visibility(pos_q, pos_k, causal, window=0):
     return vis
 
 
+def apply_block_mask(vis, block_mask, q_block_rows, k_block_rows):
+    """Block-wise sparse attention (Sec. 3.4): the rows of the query chunk and of
+    the key chunk are cut into blocks of q_block_rows / k_block_rows local rows,
+    and block_mask[a, b] != 0 says that the queries of block a may attend to the
+    keys of block b.  A pair stays visible if `vis` (full, causal or windowed)
+    allows it AND its block pair is open.  The blocks are those of the device's
+    local rows: under a split that keeps whole global blocks together (the
+    striped-like balance of Sec. 3.4) they are the global blocks."""
+    vis = np.asarray(vis, dtype=bool)
+    block_mask = np.asarray(block_mask)
+    nq, nk = vis.shape
+    qb = np.arange(nq) // q_block_rows
+    kb = np.arange(nk) // k_block_rows
+    return vis & (block_mask[qb][:, kb] != 0)
+
+
 # ---------------------------------------------------------------------------
 # The plain definition (Eq. 1 with the exclusion mask of Eq. 10) and its
 # textbook gradient.  This is what ring + merge must reproduce.

@@ -496,6 +496,57 @@ def test_windowed_attention_against_torch_sdpa_mask():
         assert np.abs(got.numpy() - want).max() < 1e-12
 
 
+# ----------------------------------------------------------------- block-wise sparse
+
+def test_block_mask_brute_force_and_block_diagonal_decouples():
+    """apply_block_mask against loops; and a block-diagonal mask makes every block an attention
+    problem of its own: O, lse and all gradients equal those of separate per-block calls."""
+    r = rng(80)
+    nq, nk, bq, bk, d = 24, 30, 8, 10, 4
+    M = (r.random((nq // bq, nk // bk)) < 0.5).astype(np.uint8)
+    base = oc.visibility(np.arange(nq) + 6, np.arange(nk), True)
+    got = oc.apply_block_mask(base, M, bq, bk)
+    for a in range(nq):
+        for b in range(nk):
+            assert got[a, b] == (base[a, b] and M[a // bq, b // bk] != 0)
+    n, blk = 24, 8
+    Q, K, V, dO = rand_qkvdo(81, n, n, d)
+    vis = oc.apply_block_mask(np.ones((n, n), bool), np.eye(n // blk, dtype=np.uint8), blk, blk)
+    O, lse = oc.attention_fwd(Q, K, V, 0.6, vis)
+    dQ, dK, dV = oc.attention_bwd(Q, K, V, dO, 0.6, vis)
+    for t in range(n // blk):
+        sl = slice(t * blk, (t + 1) * blk)
+        O_t, lse_t = oc.attention_fwd(Q[sl], K[sl], V[sl], 0.6)
+        dQ_t, dK_t, dV_t = oc.attention_bwd(Q[sl], K[sl], V[sl], dO[sl], 0.6)
+        for whole, part in ((O, O_t), (lse, lse_t), (dQ, dQ_t), (dK, dK_t), (dV, dV_t)):
+            assert np.abs(whole[sl] - part).max() < 1e-13
+
+
+def test_block_sparse_ring_equals_unsharded():
+    """Contiguous split with shard-aligned blocks: the ring over per-step block masks (sub-matrices of
+    the global one) reproduces unsharded block-sparse attention, rows with no open block included."""
+    G, N, d, blk, scale = 3, 36, 4, 4, 0.5
+    r = rng(82)
+    Q, K, V, dO = rand_qkvdo(83, N, N, d)
+    Mg = (r.random((N // blk, N // blk)) < 0.4).astype(np.uint8)
+    Mg[2, :] = 0   # a query block that sees nothing at all
+    vis_all = oc.apply_block_mask(oc.visibility(np.arange(N), np.arange(N), True), Mg, blk, blk)
+    O_ref, lse_ref = oc.attention_fwd(Q, K, V, scale, vis_all)
+    n, per = N // G, N // G // blk
+    for i in range(G):
+        pos_i = oc.contiguous_positions(i, G, N)
+        def vis_of(j):
+            pos_j = oc.contiguous_positions(j, G, N)
+            sub = Mg[i * per:(i + 1) * per, j * per:(j + 1) * per]
+            return oc.apply_block_mask(oc.visibility(pos_i, pos_j, True), sub, blk, blk)
+        O_i, lse_i = oc.ring_fwd(Q[pos_i], [K[oc.contiguous_positions(j, G, N)] for j in range(G)],
+                                 [V[oc.contiguous_positions(j, G, N)] for j in range(G)], scale, vis_of, oc.ring_order(i, G))
+        assert np.abs(O_i - O_ref[pos_i]).max() < 1e-12
+        fin = np.isfinite(lse_ref[pos_i])
+        assert (np.isfinite(lse_i) == fin).all() and np.abs(lse_i[fin] - lse_ref[pos_i][fin]).max() < 1e-12
+    assert not np.isfinite(lse_ref[2 * blk:3 * blk]).any() and (O_ref[2 * blk:3 * blk] == 0).all()
+
+
 # ----------------------------------------------------------------- planted mistakes are caught
 
 def test_planted_mistakes_fail_the_pins(monkeypatch):
