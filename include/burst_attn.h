@@ -76,6 +76,14 @@ typedef struct {
  * The zigzag split (Eq. 11-12) is two segments (front piece, back piece); the contiguous split is
  * one; the striped split (Eq. 13-14) is one segment with pos_stride = G.
  * sq == q_nseg*q_seg_len and sk == k_nseg*k_seg_len must hold.
+ * block_mask (device memory, or NULL for none) is a block-wise sparse mask of the step, the other
+ * sparse pattern of Sec. 3.4, given on LOCAL rows: byte [q_row / q_block_rows][k_row / k_block_rows]
+ * of a row-major array of ceil(sq / q_block_rows) rows with block_pitch bytes each; a pair is
+ * visible iff the mode's predicate holds AND its byte is nonzero.  q_block_rows must be a positive
+ * multiple of 256 and k_block_rows of 128 (the kernels' tiles then never straddle a block), and
+ * block_pitch >= ceil(sk / k_block_rows); chunks of more than 262144 rows are UNSUPPORTED with a
+ * block mask.  The caller owns the array; it must stay valid until the step has run on its stream.
+ * Tiles whose block is closed are neither loaded nor computed.
  */
 typedef struct {
   int32_t mode; /* burst_mask_mode_t */
@@ -84,6 +92,8 @@ typedef struct {
   int64_t q_seg_len, k_seg_len;
   int64_t pos_stride;
   int64_t window;
+  const uint8_t* block_mask; /* device, or NULL */
+  int64_t q_block_rows, k_block_rows, block_pitch;
 } burst_mask_t;
 
 /*
@@ -150,7 +160,7 @@ int burst_attn_step_bwd(const burst_shape_t* shape, const burst_mask_t* mask,
  * zigzag (Eq. 11, 0-based): device i holds [i*P,(i+1)*P) and [N-(i+1)*P, N-i*P), P = N/(2G),
  * N must be a multiple of 2G.  contiguous: device i holds [i*N/G,(i+1)*N/G).  striped (Eq. 13):
  * device i holds tokens i + G*m.  causal = 0 gives a FULL mask with the same geometry.  The helpers
- * leave window = 0; set out->window afterwards for sliding-window attention. */
+ * leave window = 0 and block_mask = NULL; set them afterwards for the sparse patterns. */
 int burst_attn_fill_zigzag_mask(int32_t dev_i, int32_t shard_j, int32_t G, int64_t N, int32_t causal,
                                 burst_mask_t* out);
 int burst_attn_fill_contiguous_mask(int32_t dev_i, int32_t shard_j, int32_t G, int64_t N,
@@ -159,7 +169,9 @@ int burst_attn_fill_striped_mask(int32_t dev_i, int32_t shard_j, int32_t G, int6
                                  int32_t causal, burst_mask_t* out);
 
 /* Number of visible (query row, key row) pairs of a step per (batch, head): the benchmark's work
- * unit (4*head_dim flop forward, 10*head_dim backward).  Returns -1 on an invalid mask. */
+ * unit (4*head_dim flop forward, 10*head_dim backward).  Returns -1 on an invalid mask.  The
+ * count is that of the mode and window alone: block_mask lives in device memory and is not read
+ * here (nor by the two tile diagnostics below). */
 int64_t burst_attn_visible_pairs(const burst_mask_t* mask);
 
 /* Host diagnostics of the tile-level mask logic, running the very code the kernels compile (no GPU

@@ -43,7 +43,8 @@ class burst_mask_t(C.Structure):
     _fields_ = [("mode", C.c_int32), ("q_nseg", C.c_int32), ("k_nseg", C.c_int32), ("_pad", C.c_int32),
                 ("q_seg_pos", C.c_int64 * 2), ("k_seg_pos", C.c_int64 * 2),
                 ("q_seg_len", C.c_int64), ("k_seg_len", C.c_int64), ("pos_stride", C.c_int64),
-                ("window", C.c_int64)]
+                ("window", C.c_int64), ("block_mask", C.c_void_p),
+                ("q_block_rows", C.c_int64), ("k_block_rows", C.c_int64), ("block_pitch", C.c_int64)]
 
 
 _P = C.POINTER
@@ -143,6 +144,16 @@ def burst_attn_fill_striped_mask(dev_i, shard_j, G, N, causal=True):
     m = burst_mask_t()
     _check(_lib.burst_attn_fill_striped_mask(dev_i, shard_j, G, N, int(causal), C.byref(m)))
     return m
+
+
+def set_block_mask(mask, block_mask, q_block_rows, k_block_rows):
+    """Attach a block-wise sparse mask (2-D uint8 device tensor, unit stride along its rows) to a
+    burst_mask_t; the tensor must outlive the steps that use the mask."""
+    if block_mask.dim() != 2 or block_mask.element_size() != 1 or block_mask.stride(1) != 1 or not block_mask.is_cuda:
+        raise ValueError("block_mask: 2-D one-byte device tensor with unit row stride expected")
+    mask.block_mask = block_mask.data_ptr()
+    mask.q_block_rows, mask.k_block_rows, mask.block_pitch = q_block_rows, k_block_rows, block_mask.stride(0)
+    return mask
 
 
 def burst_attn_visible_pairs(mask):

@@ -96,6 +96,18 @@ int check_mask(const burst_mask_t* m, int64_t sq, int64_t sk, MaskDev* out) {
   }
   out->pos_stride = (int32_t)m->pos_stride;
   out->window = (m->window == 0 || m->window >= kNoWindow) ? kNoWindow : (int32_t)m->window;
+  if (m->block_mask) {
+    if (m->q_block_rows <= 0 || m->q_block_rows % 256 != 0 || m->k_block_rows <= 0 || m->k_block_rows % 128 != 0)
+      return BURST_ERR_INVALID_ARG;
+    if (m->block_pitch < (sk + m->k_block_rows - 1) / m->k_block_rows || m->block_pitch > INT32_MAX)
+      return BURST_ERR_INVALID_ARG;
+    // the kernels cache one open flag per 64-row tile of the walked axis in LDS
+    if (sq > 64ll * kMaxBlockCacheTiles || sk > 64ll * kMaxBlockCacheTiles) return BURST_ERR_UNSUPPORTED;
+    out->blk = m->block_mask;
+    out->blk_q = (int32_t)(m->q_block_rows > INT32_MAX ? INT32_MAX - 255 : m->q_block_rows);
+    out->blk_k = (int32_t)(m->k_block_rows > INT32_MAX ? INT32_MAX - 127 : m->k_block_rows);
+    out->blk_pitch = (int32_t)m->block_pitch;
+  }
   return BURST_OK;
 }
 

@@ -85,11 +85,19 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_bwd_dq_kernel(B
   k_class.init(mk, qlo_w, qhi_w, sk, q_w0 >= q_w1);
   auto tile_class = [&](int k0_) { return k_class(mk, k0_, min(k0_ + BK, sk), k0_ + BK > sk); };   // wave-uniform
 
+  // Open flags of the key tiles against this work-group's query block (block-wise sparse mask)
+  uint8_t* open_flags = nullptr;
+  if (mk.blk) {
+    open_flags = reinterpret_cast<uint8_t*>(smem + 4 * TILE);
+    fill_open_flags<true, BK>(mk, open_flags, q_blk0, sk, tid, NT);
+    __syncthreads();
+  }
   KvWalk<D, BK, NT> walk;
-  walk.init(mk, p.k, p.v, b, hk, sk, qlo_blk, qhi_blk, tid);
+  walk.init(mk, p.k, p.v, b, hk, sk, qlo_blk, qhi_blk, tid, open_flags);
   wait_global_loads();
   int k0 = 0, cls = TILE_SKIP;   // first key row and class of the tile in LDS
-  if (walk.n_tiles > 0) {
+  bool have = walk.valid();
+  if (have) {
     walk.issue(tid);
     walk.commit(smem, smem + TILE);
     k0 = walk.k0;
@@ -98,8 +106,8 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_bwd_dq_kernel(B
   }
   __syncthreads();
   int buf = 0;
-  for (int it = 0; it < walk.n_tiles; ++it) {
-    const bool more = it + 1 < walk.n_tiles;
+  while (have) {
+    const bool more = walk.valid();
     int k0n = 0, cls_n = TILE_SKIP;
     if (more) {
       walk.issue(tid);
@@ -131,6 +139,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_bwd_dq_kernel(B
     buf ^= 1;
     k0 = k0n;
     cls = cls_n;
+    have = more;
   }
 
   if (q_w0 + r < sq) {
@@ -218,7 +227,7 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
   // consecutive tiles; inside a run the cursor moves by adding constants, and only a run or head
   // change recomputes addresses.
   const TileRuns qr = visible_tiles<true, BQ>(mk, klo_blk, khi_blk, sq);
-  const int n_items = group * qr.total();
+  bool c_valid = qr.total() > 0;                   // the cursor is on an item
   int c_run = 0, c_left = qr.len[0], c_head = 0;   // cursor: run, tiles left in it, head of the group
   int q0n = qr.start[0] * BQ;                      // first row of the tile under the cursor
 
@@ -239,7 +248,16 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
                                             (int64_t)q0n * p.d_o.ss);
     row_head = tid < BQ ? p.lse.ptr + b * p.lse.sb + hq * p.lse.sh : p.d.ptr + b * p.d.sb + hq * p.d.sh;
   };
-  auto advance = [&]() {   // cursor to the next item
+  // Open flags of the query tiles against this work-group's key block (block-wise sparse mask)
+  const uint8_t* open_flags = nullptr;
+  if (mk.blk) {
+    uint8_t* flags = reinterpret_cast<uint8_t*>(smem + L::BYTES);
+    if (ROLE == 0) fill_open_flags<false, BQ>(mk, flags, k_blk0, sq, tid, NT);
+    open_flags = flags;
+    __syncthreads();
+  }
+  auto is_open = [&](int q0_) { return !open_flags || __builtin_amdgcn_readfirstlane(open_flags[q0_ / BQ]) != 0; };
+  auto step = [&]() {   // cursor to the next tile of the walk
     if (--c_left > 0) {
       q0n += BQ;
       q_tile += q_step;
@@ -254,7 +272,12 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
       c_left = c_run ? qr.len[1] : qr.len[0];
       q0n = (c_run ? qr.start[1] : qr.start[0]) * BQ;
       if (c_head < group) point();
+      else c_valid = false;
     }
+  };
+  auto advance = [&]() {   // cursor to the next item: the next tile that the block mask leaves open
+    do step();
+    while (c_valid && !is_open(q0n));
   };
   auto issue = [&]() {   // loads of the tile under the cursor
     if (ROLE != 0) return;
@@ -278,8 +301,12 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
 
   wait_global_loads();
   int q0 = 0, cls = TILE_SKIP;   // first row and class of the tile in slot (qs_cur, par)
-  if (n_items > 0) {
+  if (c_valid) {
     point();
+    if (!is_open(q0n)) advance();
+  }
+  bool have = c_valid;
+  if (have) {
     issue();
     commit(0, 0);
     q0 = q0n;
@@ -290,9 +317,9 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
   int qs_prev = 2, qs_cur = 0, qs_next = 1, par = 0;
   int cls_prev = TILE_SKIP;
   f32x16 dp[QBK];   // dS-wave: dP of the tile staged one iteration ago
-  // n_items + 1 iterations: the last one only drains the dS-wave's lagging half
-  for (int it = 0; it <= n_items; ++it) {
-    const bool more = it + 1 < n_items;
+  // one iteration per item and a last one that only drains the dS-wave's lagging half
+  for (;;) {
+    const bool more = have && c_valid;
     int q0_next = 0, cls_next = TILE_SKIP;
     if (more) {
       issue();
@@ -368,6 +395,8 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
     cls_prev = cls;
     q0 = q0_next;
     cls = cls_next;
+    if (!have) break;
+    have = more;
   }
 
   if (k_w0 + r < sk) {
@@ -406,7 +435,7 @@ static hipError_t launch_bwd_t(BwdParams p, hipStream_t stream) {
   hipError_t e = hipSuccess;
   if (p.dq.ptr) {
     constexpr int KB = BURST_DQ_KB;
-    constexpr int LDS = 2 * 2 * 32 * KB * (2 * D + 16);
+    constexpr int LDS = 2 * 2 * 32 * KB * (2 * D + 16) + kMaxBlockCacheTiles;
     p.q_runs = nonempty_runs(p.mask, p.sq, p.sk, kDqBQ, true);
     // query tiles that see no key get no work-group: "=" must still leave zeros there
     if (!p.acc_dq && p.q_runs.total() < (p.sq + kDqBQ - 1) / kDqBQ) {
@@ -422,7 +451,7 @@ static hipError_t launch_bwd_t(BwdParams p, hipStream_t stream) {
   }
   if (p.dk.ptr) {
     constexpr int BQ = 64;
-    constexpr int LDS = DkdvLds<D, BQ>::BYTES;
+    constexpr int LDS = DkdvLds<D, BQ>::BYTES + kMaxBlockCacheTiles;
     p.k_runs = nonempty_runs(p.mask, p.sq, p.sk, 128, false);
     if (p.k_runs.total() < (p.sk + 127) / 128) {
       if (!p.acc_dk) e = launch_zero_tensor(p.dk, p.batch, p.sk, p.kv_heads, p.head_dim, stream);

@@ -47,7 +47,25 @@ struct MaskDev {
   int32_t q_seg_pos[2], k_seg_pos[2];
   int32_t pos_stride;
   int32_t window;   // causal only: pos(q) - pos(k) < window as well; kNoWindow = unlimited
+  // Block-wise sparse mask over local rows (nullptr: none): byte [q_row / blk_q][k_row / blk_k],
+  // row pitch blk_pitch bytes, nonzero = the block pair is open.  blk_q is a multiple of 256 and
+  // blk_k of 128 (checked on the host), so every tile of every kernel lies inside one block pair.
+  const uint8_t* blk;
+  int32_t blk_q, blk_k, blk_pitch;
 };
+constexpr int kMaxBlockCacheTiles = 4096;   // tiles of the walked axis whose open flags fit the LDS cache
+
+// Open flags of the tiles of one axis against a fixed block of the other, cached in LDS once per
+// work-group: flags[t] for tile t of TILE rows.  fixed_row: any row of the fixed block.
+template <bool WALK_KEYS, int TILE>
+__device__ __forceinline__ void fill_open_flags(const MaskDev& mk, uint8_t* flags, int fixed_row, int rows, int tid, int nthreads) {
+  const int n = (rows + TILE - 1) / TILE;
+  for (int t = tid; t < n; t += nthreads) {
+    const int q_blk = WALK_KEYS ? fixed_row / mk.blk_q : (t * TILE) / mk.blk_q;
+    const int k_blk = WALK_KEYS ? (t * TILE) / mk.blk_k : fixed_row / mk.blk_k;
+    flags[t] = mk.blk[(int64_t)q_blk * mk.blk_pitch + k_blk];
+  }
+}
 constexpr int32_t kNoWindow = 0x7fffffff;   // no position difference reaches it (positions < 2^31 - 1)
 
 // Rows r in [0, seg_len) of a segment with r * stride < gap / with r * stride <= room (64-bit: the
@@ -377,18 +395,19 @@ template <int D, int BK, int NT>
 struct KvWalk {
   TileStager<D, BK, NT> stage_k, stage_v;
   TileRuns runs;
-  int n_tiles;            // tiles the walk visits
-  int run, left, k0;      // cursor: run, tiles left in it, first key row of its tile
+  int run, left, k0;      // cursor: run, tiles left in it (0: the walk is over), first key row of its tile
   int sk;
+  const uint8_t* open;    // LDS flags per key tile from a block-wise sparse mask, or nullptr
   const char *k_base, *v_base, *k_tile, *v_tile;   // row 0 of the head; first row of the cursor's tile
   int64_t k_row, v_row;   // bytes per key row
 
-  // [q_lo, q_hi]: positions spanned by the query rows of the work-group
+  // [q_lo, q_hi]: positions spanned by the query rows of the work-group.  The cursor starts on the
+  // first tile to visit.
   __device__ __forceinline__ void init(const MaskDev& mk, const TensorDev& k, const TensorDev& v, int b, int hk, int sk_,
-                                       int q_lo, int q_hi, int tid) {
+                                       int q_lo, int q_hi, int tid, const uint8_t* open_flags) {
     sk = sk_;
+    open = open_flags;
     runs = visible_tiles<false, BK>(mk, q_lo, q_hi, sk);
-    n_tiles = runs.total();
     run = 0;
     left = runs.len[0];
     k0 = runs.start[0] * BK;
@@ -400,7 +419,9 @@ struct KvWalk {
     v_tile = v_base + k0 * v_row;
     stage_k.init(k.ss, tid);
     stage_v.init(v.ss, tid);
+    seek();
   }
+  __device__ __forceinline__ bool valid() const { return left > 0; }
   __device__ __forceinline__ void issue(int tid) {   // loads of the cursor's tile
     if (k0 + BK <= sk) {
       stage_k.load_at(k_tile);
@@ -410,18 +431,28 @@ struct KvWalk {
       stage_v.load(reinterpret_cast<const __bf16*>(v_base), v_row >> 1, k0, sk, tid);
     }
   }
-  __device__ __forceinline__ void advance() {
+  __device__ __forceinline__ void step() {
     if (--left > 0) {
       k0 += BK;
       k_tile += BK * k_row;
       v_tile += BK * v_row;
-    } else {
+    } else if (run == 0) {
       run = 1;
       left = runs.len[1];
       k0 = runs.start[1] * BK;
       k_tile = k_base + k0 * k_row;
       v_tile = v_base + k0 * v_row;
     }
+  }
+  // skip tiles that the block mask closes
+  __device__ __forceinline__ void seek() {
+    if (open) {
+      while (left > 0 && __builtin_amdgcn_readfirstlane(open[k0 / BK]) == 0) step();
+    }
+  }
+  __device__ __forceinline__ void advance() {
+    step();
+    seek();
   }
   __device__ __forceinline__ void commit(char* k_lds, char* v_lds) const {
     stage_k.store(k_lds);

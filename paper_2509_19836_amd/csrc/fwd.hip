@@ -66,11 +66,19 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
   k_class.init(mk, qlo_w, qhi_w, sk, q_w0 >= q_w1);
   auto tile_class = [&](int k0_) { return k_class(mk, k0_, min(k0_ + BK, sk), k0_ + BK > sk); };   // wave-uniform
 
+  // Open flags of the key tiles against this work-group's query block (block-wise sparse mask)
+  uint8_t* open_flags = nullptr;
+  if (mk.blk) {
+    open_flags = reinterpret_cast<uint8_t*>(smem + 4 * TILE);
+    fill_open_flags<true, BK>(mk, open_flags, q_blk0, sk, tid, NT);
+    __syncthreads();
+  }
   KvWalk<D, BK, NT> walk;
-  walk.init(mk, p.k, p.v, b, hk, sk, qlo_blk, qhi_blk, tid);
+  walk.init(mk, p.k, p.v, b, hk, sk, qlo_blk, qhi_blk, tid, open_flags);
   wait_global_loads();
   int k0 = 0, cls = TILE_SKIP;   // first key row and class of the tile in LDS
-  if (walk.n_tiles > 0) {
+  bool have = walk.valid();
+  if (have) {
     walk.issue(tid);
     walk.commit(smem, smem + TILE);
     k0 = walk.k0;
@@ -79,8 +87,8 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
   }
   __syncthreads();
   int buf = 0;
-  for (int it = 0; it < walk.n_tiles; ++it) {
-    const bool more = it + 1 < walk.n_tiles;
+  while (have) {
+    const bool more = walk.valid();
     int k0n = 0, cls_n = TILE_SKIP;
     if (more) {
       walk.issue(tid);
@@ -150,6 +158,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
     buf ^= 1;
     k0 = k0n;
     cls = cls_n;
+    have = more;
   }
 
   // Epilogue: normalise, Lse in natural-log units, optional online-softmax merge.
@@ -236,7 +245,7 @@ __global__ __launch_bounds__(256) void fwd_fill_dead_rows_kernel(FwdParams p) {
 template <int D>
 static hipError_t launch_fwd_t(FwdParams p, hipStream_t stream) {
   constexpr int BQ = kFwdBQ;
-  constexpr int LDS = 2 * 2 * 64 * (2 * D + 16);
+  constexpr int LDS = 2 * 2 * 64 * (2 * D + 16) + kMaxBlockCacheTiles;
   p.q_runs = nonempty_runs(p.mask, p.sq, p.sk, BQ, true);
   const int n_tiles = (p.sq + BQ - 1) / BQ;
   if (p.o_part.ptr && p.q_runs.total() < n_tiles) {

@@ -31,7 +31,7 @@ def test_struct_layouts_match_the_header(lib):
     assert C.sizeof(lib.burst_shape_t) == 40
     assert C.sizeof(lib.burst_tensor_t) == 40
     assert C.sizeof(lib.burst_rowvec_t) == 24
-    assert C.sizeof(lib.burst_mask_t) == 16 + 32 + 32
+    assert C.sizeof(lib.burst_mask_t) == 16 + 32 + 32 + 32
 
 
 @pytest.mark.parametrize("G,N", [(1, 8), (2, 24), (4, 64), (8, 128)])
@@ -125,6 +125,16 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert fwd(mask=lib.burst_mask_t(1, 1, 1, 0, (0, 0), (0, 0), 64, 64, 1, -3)) == INV    # negative window
     assert fwd(mask=lib.burst_mask_t(0, 1, 1, 0, (0, 0), (0, 0), 64, 64, 1, 16)) == INV    # window without causal
     assert fwd(k=_fake_tensor(lib, strides=(1 << 40, (1 << 24) + 8, 128))) == UNS          # row stride beyond 2^24
+
+    def blk(q_rows, k_rows, pitch, sq=64, sk=64):
+        m = lib.burst_mask_t(1, 1, 1, 0, (0, 0), (0, 0), sq, sk, 1, 0, 0x10000, q_rows, k_rows, pitch)
+        return fwd(shape=lib.shape(1, 2, 2, 128, sq, sk, 0.1), mask=m)
+    assert blk(128, 128, 1) == INV          # query blocks must be multiples of 256 rows
+    assert blk(256, 64, 1) == INV           # key blocks of 128
+    assert blk(0, 128, 1) == INV
+    assert blk(256, 128, 0) == INV          # pitch below the number of key blocks
+    assert blk(256, 128, 3, sk=512) == INV
+    assert blk(256, 128, 4096, sq=64 * 4096 + 64) == UNS   # more tiles than the kernels' flag cache holds
 
     def bwd(dq=tf32, dk=tf32, dv=tf32, flags=0, lse=rv, d=rv, d_o=t):
         ref = lambda x: None if x is None else r(x)
