@@ -29,7 +29,23 @@ PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flo
 PROFILED_TRAFFIC_BYTES = {2: 1.873e9}
 
 
-def cpu_baseline(w, kind, dev_i, shards, sample_rows, seed, window=0):
+def block_masked_pairs(bm, pos_q, pos_k, R, causal, window):
+    """Visible pairs of a step under a local block mask: per open block pair, the pairs that the
+    mode and the window leave, a function of the offset between the two blocks' first positions."""
+    import numpy as np
+    memo, total = {}, 0
+    ar = np.arange(R)
+    for a, b in zip(*np.nonzero(bm)):
+        off = int(pos_q[a * R] - pos_k[b * R])
+        if off not in memo:
+            diff = off + ar[:, None] - ar[None, :]
+            ok = np.ones_like(diff, dtype=bool) if not causal else (diff >= 0) & ((diff < window) if window else True)
+            memo[off] = int(ok.sum())
+        total += memo[off]
+    return total
+
+
+def cpu_baseline(w, kind, dev_i, shards, sample_rows, seed, window=0, pattern=None, block_rows=0):
     """The fp64 oracle, untuned, on a bounded sample of the same workload: `sample_rows` query rows
     (evenly spaced over the chunk) of one (batch, head) against each of the whole KV shards in
     `shards`, forward step + D + backward step per shard.  Returns TFLOPS with the same
@@ -49,7 +65,11 @@ def cpu_baseline(w, kind, dev_i, shards, sample_rows, seed, window=0):
     for shard_j in shards:
         kpos = pos_fn(shard_j, G, N)
         K, V = draw(kpos.size), draw(kpos.size)
-        vis = oc.visibility(qpos_all[sel], kpos, kind != "full", window)
+        if pattern is None:
+            vis = oc.visibility(qpos_all[sel], kpos, kind != "full", window)
+        else:
+            bm = wl.local_block_mask(pattern, qpos_all, kpos, block_rows)
+            vis = oc.apply_block_mask(oc.visibility(qpos_all, kpos, kind != "full", window), bm, block_rows, block_rows)[sel]
         pairs += int(vis.sum())
         t0 = time.perf_counter()
         O, lse = oc.step_fwd(Q, K, V, w.scale, vis)
@@ -80,6 +100,10 @@ def main():
                                                            "not the headline metric, for the sparse rows")
     ap.add_argument("--partition", default=None, choices=["zigzag", "striped", "causal", "full"],
                     help="override the workload's partition / mask kind")
+    ap.add_argument("--block-density", type=float, default=0.0,
+                    help="block-wise sparse attention: fraction of open blocks of a seeded random pattern over "
+                         "global token blocks, diagonal always open (0 = no block mask); not the headline metric")
+    ap.add_argument("--block-rows", type=int, default=512, help="rows of a (square) block of that pattern")
     ap.add_argument("--cpu-shards", type=int, default=4, help="KV shards the CPU baseline sample covers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -117,6 +141,18 @@ def main():
     order = ring.ring_order(i, G)
     masks = {j: ring.fill_mask(kind, i, j, G, N, args.window) for j in order}
     pairs = {j: lib.burst_attn_visible_pairs(masks[j]) for j in order}
+    pattern, block_masks = None, []
+    if args.block_density > 0:
+        if kind == "striped":
+            sys.exit("bench.py: a pattern over blocks of consecutive tokens does not map to row blocks of the striped split")
+        R = args.block_rows
+        pattern = wl.block_sparse_pattern(N // R, args.block_density, wl.BASE_SEED + 77)
+        for j in order:
+            pos_q, pos_k = ring.mask_positions(masks[j], "q"), ring.mask_positions(masks[j], "k")
+            bm = wl.local_block_mask(pattern, pos_q, pos_k, R)
+            block_masks.append(torch.from_numpy(bm).cuda())   # kept alive for the whole run
+            lib.set_block_mask(masks[j], block_masks[-1], R, R)
+            pairs[j] = block_masked_pairs(bm, pos_q, pos_k, R, kind != "full", args.window)
     shp = lib.shape(B, Hq, Hkv, d, n, n, w.scale)
     DQ, DKV = lib.BURST_ACC_DQ, lib.BURST_ACC_DK | lib.BURST_ACC_DV
     ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -226,7 +262,9 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name} (config {args.config}): device {i} of {G}, one full simulated ring = "
                                f"{G} fwd steps + D + {G} bwd steps, B={B} Hq={Hq} Hkv={Hkv} d={d}, "
-                               f"Q chunk {n} x {G} KV chunks of {n}, mask {kind}" + (f", window {args.window}" if args.window else ""),
+                               f"Q chunk {n} x {G} KV chunks of {n}, mask {kind}" + (f", window {args.window}" if args.window else "")
+                               + (f", block-sparse pattern of density {args.block_density} over {args.block_rows}-token blocks"
+                                  if pattern is not None else ""),
                    "ring_steps_per_step": G, "ms_per_ring_step": round(ms_ring / G, 3)},
         "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
         "fwd_tflops": round(fl_fwd / (fwd_ms * 1e-3) / 1e12, 2),
@@ -239,12 +277,12 @@ def main():
         "pct_of_random_operand_mfma_ceiling": round(100 * value / ceiling["random_operands"], 2),
         "roofline": {"bound": "mfma", "kernel": "step_bwd_dkdv_kernel", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": PROFILED_TRAFFIC_BYTES.get(args.config) if (i == 3 and not args.window and not args.partition) else None,
+                     "traffic": PROFILED_TRAFFIC_BYTES.get(args.config) if (i == 3 and not args.window and not args.partition and pattern is None) else None,
                      "issued_tflops": round(per_launch_pairs * 8 * d / (avg["step_bwd_dkdv"] * 1e-3) / 1e12, 2)},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, kind, i, order[1:1 + args.cpu_shards] or order[:1], args.cpu_sample_rows,
-                                           wl.BASE_SEED + 5, args.window)
+                                           wl.BASE_SEED + 5, args.window, pattern, args.block_rows)
     print(json.dumps(out))
 
 

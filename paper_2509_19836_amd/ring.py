@@ -30,6 +30,14 @@ def fill_mask(kind, i, j, G, N, window=0):
     return m
 
 
+def mask_positions(mask, side):
+    """Global token positions of the local rows of the "q" or "k" side of a burst_mask_t."""
+    import numpy as np
+    nseg, seg_len, seg_pos = ((mask.q_nseg, mask.q_seg_len, mask.q_seg_pos) if side == "q" else
+                              (mask.k_nseg, mask.k_seg_len, mask.k_seg_pos))
+    return np.concatenate([seg_pos[s] + np.arange(seg_len, dtype=np.int64) * mask.pos_stride for s in range(nseg)])
+
+
 def ring_forward(i, G, N, kind, scale, q_i, k_shards, v_shards, o_acc, lse_acc, stream=None, window=0):
     """o_acc / lse_acc must hold (0, -inf) on entry; they hold (O_i, Lse_i) on return."""
     B, n, Hq, d = q_i.shape

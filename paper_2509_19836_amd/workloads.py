@@ -99,3 +99,27 @@ def host_tensors(w, cfg_index=0, seed_offset=0):
         x = _draw(base + n, shape, w.head_scale and name != "do")
         out[name] = (x, f32_to_bf16_bits(x))
     return out
+
+
+def block_sparse_pattern(n_blocks, density, seed):
+    """Seeded block-sparse attention pattern over global token blocks: an n_blocks x n_blocks uint8
+    matrix (row: query block, column: key block) whose entries are open with probability `density`,
+    with the diagonal always open so that every token keeps at least itself."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    pat = (rng.random((n_blocks, n_blocks)) < density).astype(np.uint8)
+    np.fill_diagonal(pat, 1)
+    return pat
+
+
+def local_block_mask(pattern, pos_q, pos_k, block_rows):
+    """The slice of a global block pattern that a ring step sees, on LOCAL row blocks: entry
+    [a][b] is the pattern entry of the global blocks holding local rows a*block_rows and
+    b*block_rows.  pos_q / pos_k: global positions of the local rows; every local block must lie
+    inside one global block (true for the contiguous and zigzag splits when block_rows divides the
+    piece length)."""
+    pos_q, pos_k = np.asarray(pos_q), np.asarray(pos_k)
+    for pos in (pos_q, pos_k):
+        first, last = pos[::block_rows] // block_rows, pos[block_rows - 1::block_rows] // block_rows
+        if pos.size % block_rows or not np.array_equal(first, last):
+            raise ValueError("local row blocks straddle global blocks")
+    return np.ascontiguousarray(pattern[np.ix_(pos_q[::block_rows] // block_rows, pos_k[::block_rows] // block_rows)])

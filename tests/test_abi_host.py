@@ -303,3 +303,29 @@ def test_tile_logic_rejects_bad_arguments(lib):
     out = (C.c_int32 * 4)()
     assert raw.burst_attn_visible_tile_runs(C.byref(m), 1, 48, 0, 1, C.byref(out)) == lib.BURST_ERR_UNSUPPORTED
     assert raw.burst_attn_visible_tile_runs(C.byref(m), 1, 64, 5, 5, C.byref(out)) == lib.BURST_ERR_INVALID_ARG
+
+
+def test_block_pattern_slices_and_pair_counts(lib):
+    """Host logic of the block-sparse benchmark workload: the per-step slice of a global block
+    pattern, and the count of visible pairs under it, against the oracle's visibility matrix."""
+    import bench
+    from oracle import burst_oracle as oc
+    from paper_2509_19836_amd import ring, workloads as wl
+    G, N, R = 2, 2048, 256
+    pattern = wl.block_sparse_pattern(N // R, 0.5, 11)
+    assert pattern.shape == (8, 8) and pattern.diagonal().all() and 0 < pattern.sum() < 64
+    for kind, window in (("zigzag", 0), ("causal", 0), ("causal", 300), ("full", 0)):
+        for i in range(G):
+            for j in range(G):
+                m = ring.fill_mask(kind, i, j, G, N, window)
+                pos_q, pos_k = ring.mask_positions(m, "q"), ring.mask_positions(m, "k")
+                bm = wl.local_block_mask(pattern, pos_q, pos_k, R)
+                # brute force: the pattern entry of the global blocks of each (q, k) pair
+                want = pattern[np.ix_(pos_q // R, pos_k // R)].astype(bool)
+                vis = oc.visibility(pos_q, pos_k, kind != "full", window)
+                masked = oc.apply_block_mask(vis, bm, R, R)
+                assert np.array_equal(masked, vis & want)
+                assert bench.block_masked_pairs(bm, pos_q, pos_k, R, kind != "full", window) == int(masked.sum())
+    with pytest.raises(ValueError):   # striped rows do not form blocks of consecutive tokens
+        m = ring.fill_mask("striped", 0, 1, G, N)
+        wl.local_block_mask(pattern, ring.mask_positions(m, "q"), ring.mask_positions(m, "k"), R)
