@@ -72,6 +72,19 @@ _lib.burst_attn_visible_tile_runs.restype = C.c_int
 _lib.burst_attn_visible_tile_runs.argtypes = [_P(burst_mask_t), C.c_int32, C.c_int32, C.c_int64, C.c_int64, _P(C.c_int32 * 4)]
 _lib.burst_attn_mfma_probe.restype = C.c_int
 _lib.burst_attn_mfma_probe.argtypes = [C.c_int32, C.c_int32, C.c_void_p, _P(C.c_int64), C.c_void_p]
+
+
+class burst_lm_head_shape_t(C.Structure):
+    _fields_ = [("n_tokens", C.c_int64), ("d_model", C.c_int64), ("vocab", C.c_int64), ("tile_tokens", C.c_int64),
+                ("grad_scale", C.c_float), ("_pad", C.c_int32)]
+
+
+_lib.burst_lm_head_workspace_bytes.restype = C.c_int64
+_lib.burst_lm_head_workspace_bytes.argtypes = [_P(burst_lm_head_shape_t)]
+_lib.burst_lm_head_loss.restype = C.c_int
+_lib.burst_lm_head_loss.argtypes = [_P(burst_lm_head_shape_t), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_int64,
+                                    C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
 _lib.burst_attn_status_string.restype = C.c_char_p
 _lib.burst_attn_status_string.argtypes = [C.c_int]
 _lib.burst_attn_last_hip_error.restype = C.c_int
@@ -80,7 +93,7 @@ _lib.burst_attn_version.restype = C.c_char_p
 EXPORTS = ["burst_attn_step_fwd", "burst_attn_lse_merge", "burst_attn_preprocess_bwd", "burst_attn_step_bwd",
            "burst_attn_fill_zigzag_mask", "burst_attn_fill_contiguous_mask", "burst_attn_fill_striped_mask",
            "burst_attn_visible_pairs", "burst_attn_tile_class", "burst_attn_visible_tile_runs", "burst_attn_mfma_probe", "burst_attn_status_string", "burst_attn_last_hip_error",
-           "burst_attn_version"]
+           "burst_attn_version", "burst_lm_head_workspace_bytes", "burst_lm_head_loss"]
 
 
 class BurstError(RuntimeError):
@@ -204,6 +217,36 @@ def burst_attn_step_bwd(shp, mask, q, k, v, d_o, lse, d, dq=None, dk=None, dv=No
     _check(_lib.burst_attn_step_bwd(C.byref(shp), _ref(mask), _ref(tensor(q)), _ref(tensor(k)), _ref(tensor(v)),
                                     _ref(tensor(d_o)), _ref(rowvec(lse)), _ref(rowvec(d)), _ref(tensor(dq)),
                                     _ref(tensor(dk)), _ref(tensor(dv)), accumulate_flags, _stream(stream)))
+
+
+def lm_head_shape(n_tokens, d_model, vocab, tile_tokens, grad_scale=1.0):
+    return burst_lm_head_shape_t(n_tokens, d_model, vocab, tile_tokens, grad_scale, 0)
+
+
+def burst_lm_head_workspace_bytes(shp):
+    n = _lib.burst_lm_head_workspace_bytes(C.byref(shp))
+    if n < 0:
+        raise BurstError(BURST_ERR_INVALID_ARG)
+    return n
+
+
+def burst_lm_head_loss(shp, h_last, w_head, y, loss, workspace, lse=None, d_h=None, d_w=None, accumulate_dw=False,
+                       stream=None):
+    """h_last [N, d] bf16, w_head [v, d] bf16, y [N] int64, loss / lse [N] fp32, d_h [N, d] fp32 or bf16,
+    d_w [v, d] fp32, workspace: one-byte tensor of burst_lm_head_workspace_bytes(shp) bytes.  Rows may be
+    strided; the last dimension is contiguous."""
+    for t in (h_last, w_head, d_h, d_w):
+        assert t is None or (t.dim() == 2 and t.stride(1) == 1), "expected 2-D tensors with a contiguous last dim"
+    assert h_last.dtype == torch.bfloat16 and w_head.dtype == torch.bfloat16 and y.dtype == torch.int64
+    assert y.is_contiguous() and loss.is_contiguous() and loss.dtype == torch.float32
+    assert lse is None or (lse.is_contiguous() and lse.dtype == torch.float32)
+    assert d_w is None or d_w.dtype == torch.float32
+    ptr = lambda t: None if t is None else C.c_void_p(t.data_ptr())
+    dh_dtype = BURST_F32 if d_h is None else {torch.bfloat16: BURST_BF16, torch.float32: BURST_F32}[d_h.dtype]
+    _check(_lib.burst_lm_head_loss(C.byref(shp), ptr(h_last), h_last.stride(0), ptr(w_head), w_head.stride(0), ptr(y),
+                                   ptr(loss), ptr(lse), ptr(d_h), dh_dtype, 0 if d_h is None else d_h.stride(0),
+                                   ptr(d_w), 0 if d_w is None else d_w.stride(0), int(accumulate_dw),
+                                   ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def burst_attn_mfma_probe(random_operands, iterations, stream=None):

@@ -5,6 +5,7 @@
 #include <cstring>
 
 #include "../../include/burst_attn.h"
+#include "../../include/burst_lm_head.h"
 #include "kernels.hpp"
 
 using namespace burst;
@@ -381,6 +382,77 @@ int burst_attn_mfma_probe(int32_t random_operands, int32_t iterations, float* si
                           void* hip_stream) {
   if (iterations < 1 || iterations > (1 << 24)) return BURST_ERR_INVALID_ARG;
   hipError_t e = launch_mfma_probe(sink, iterations, random_operands != 0, flops_out, (hipStream_t)hip_stream);
+  return e == hipSuccess ? BURST_OK : hip_fail(e);
+}
+
+static int check_lm_shape(const burst_lm_head_shape_t* s) {
+  if (!s) return BURST_ERR_INVALID_ARG;
+  if (s->n_tokens < 0 || s->d_model < 1 || s->vocab < 1 || s->tile_tokens < 1 || s->tile_tokens % 256 != 0)
+    return BURST_ERR_INVALID_ARG;
+  if (!std::isfinite(s->grad_scale)) return BURST_ERR_INVALID_ARG;
+  if (s->d_model % 256 != 0) return BURST_ERR_UNSUPPORTED;
+  // 32-bit row indices in the kernels and 32-bit byte offsets inside a staged tile
+  if (s->n_tokens > INT32_MAX - 256 || s->vocab > ((int64_t)1 << 22) || s->d_model > ((int64_t)1 << 22) ||
+      s->tile_tokens > ((int64_t)1 << 20))
+    return BURST_ERR_UNSUPPORTED;
+  return BURST_OK;
+}
+
+int64_t burst_lm_head_workspace_bytes(const burst_lm_head_shape_t* shape) {
+  if (check_lm_shape(shape) != BURST_OK) return -1;
+  return lm_head_workspace_bytes(shape->tile_tokens, shape->vocab);
+}
+
+int burst_lm_head_loss(const burst_lm_head_shape_t* shape, const void* h_last, int64_t ld_h, const void* w_head,
+                       int64_t ld_w, const int64_t* y, float* loss, float* lse, void* d_h, int32_t d_h_dtype,
+                       int64_t ld_dh, float* d_w, int64_t ld_dw, int32_t accumulate_dw, void* workspace,
+                       int64_t workspace_bytes, void* hip_stream) {
+  BURST_TRY(check_lm_shape(shape));
+  const int64_t d = shape->d_model, max_ld = (int64_t)1 << 22;
+  auto aligned = [](const void* ptr, uintptr_t a) { return ptr && (reinterpret_cast<uintptr_t>(ptr) % a) == 0; };
+  if (!aligned(w_head, 16)) return BURST_ERR_INVALID_ARG;
+  if (shape->n_tokens > 0 && (!aligned(h_last, 16) || !aligned(y, 8) || !aligned(loss, 4))) return BURST_ERR_INVALID_ARG;
+  if (lse && !aligned(lse, 4)) return BURST_ERR_INVALID_ARG;
+  if (ld_h < d || ld_h % 8 != 0 || ld_w < d || ld_w % 8 != 0) return BURST_ERR_INVALID_ARG;
+  if (ld_h > max_ld || ld_w > max_ld) return BURST_ERR_UNSUPPORTED;
+  if (d_h) {
+    if (d_h_dtype != BURST_F32 && d_h_dtype != BURST_BF16) return BURST_ERR_INVALID_ARG;
+    if (!aligned(d_h, 16) || ld_dh < d || ld_dh % 8 != 0) return BURST_ERR_INVALID_ARG;
+    if (ld_dh > max_ld) return BURST_ERR_UNSUPPORTED;
+  }
+  if (d_w) {
+    if (!aligned(d_w, 16) || ld_dw < d || ld_dw % 4 != 0) return BURST_ERR_INVALID_ARG;
+    if (ld_dw > max_ld) return BURST_ERR_UNSUPPORTED;
+  }
+  if (!aligned(workspace, 256) || workspace_bytes < lm_head_workspace_bytes(shape->tile_tokens, shape->vocab))
+    return BURST_ERR_INVALID_ARG;
+  LmHeadParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.n_tokens = (int32_t)shape->n_tokens;
+  p.d_model = (int32_t)d;
+  p.vocab = (int32_t)shape->vocab;
+  p.tile_tokens = (int32_t)shape->tile_tokens;
+  p.v_pad = (int32_t)((shape->vocab + 255) / 256 * 256);
+  p.grad_scale = shape->grad_scale;
+  p.h = (const __bf16*)h_last;
+  p.w = (const __bf16*)w_head;
+  p.ld_h = ld_h;
+  p.ld_w = ld_w;
+  p.y = y;
+  p.loss = loss;
+  p.lse = lse;
+  p.dh = d_h;
+  p.dh_is_f32 = d_h_dtype == BURST_F32;
+  p.ld_dh = ld_dh;
+  p.dw = d_w;
+  p.ld_dw = ld_dw;
+  p.acc_dw = accumulate_dw != 0;
+  char* ws = (char*)workspace;
+  const int64_t cells = (int64_t)p.tile_tokens * p.v_pad;
+  p.logits = (float*)ws;
+  p.dlogits = (__bf16*)(ws + cells * 4);
+  p.part = (float2*)(ws + cells * 6);
+  hipError_t e = launch_lm_head_loss(p, (hipStream_t)hip_stream);
   return e == hipSuccess ? BURST_OK : hip_fail(e);
 }
 

@@ -236,6 +236,13 @@ __device__ __forceinline__ int lds_row(int tile_row) {
   // tile row 16c + 4a + b  ->  LDS row 16c + 4b + a
   return (tile_row & ~15) | ((tile_row & 3) << 2) | ((tile_row >> 2) & 3);
 }
+// Variant for tiles whose rows are the contraction index of a GEMM whose other operand is read
+// row-wise: tile row 16c + 8h + 4t + j -> LDS row 16c + 4j + 2t + h, so that the column-wise operand
+// read hands half-wave h the rows 16c + 8h .. 8h+7 in order, the same eight k that lds_rows_operand
+// hands it (with lds_row it would be rows 4h..4h+3 and 8+4h..8+4h+3, the accumulator order).
+__device__ __forceinline__ int lds_row_k8(int tile_row) {
+  return (tile_row & ~15) | ((tile_row & 3) << 2) | (((tile_row >> 2) & 1) << 1) | ((tile_row >> 3) & 1);
+}
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -339,7 +346,7 @@ __host__ __device__ __forceinline__ TileRuns visible_tiles(const MaskDev& mk, in
 // with.  The per-lane part of the address is one 32-bit element offset computed once; the
 // per-tile and per-pass parts are wave-uniform, so a load costs no vector arithmetic.  Tiles that
 // reach past the last row take a slower path that clamps row indices instead.
-template <int D, int ROWS, int THREADS = 256>
+template <int D, int ROWS, int THREADS = 256, bool K8 = false>   // K8: rows permuted by lds_row_k8
 struct TileStager {
   static constexpr int CPR = D / 8;              // 16-byte chunks per row
   static constexpr int RPP = THREADS / CPR;      // rows per pass
@@ -355,7 +362,7 @@ struct TileStager {
     lane_off = (uint32_t)(tid / CPR) * (uint32_t)ss + (uint32_t)(tid % CPR) * 8u;
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
-      lds_off[i] = lds_row(tid / CPR + i * RPP) * PITCH + (tid % CPR) * 16;
+      lds_off[i] = (K8 ? lds_row_k8(tid / CPR + i * RPP) : lds_row(tid / CPR + i * RPP)) * PITCH + (tid % CPR) * 16;
       src_off[i] = 2u * ((uint32_t)(tid / CPR + i * RPP) * (uint32_t)ss + (uint32_t)(tid % CPR) * 8u);
     }
   }

@@ -79,6 +79,30 @@ inline TileRuns nonempty_runs(const MaskDev& mk, int sq, int sk, int tile_rows, 
   return tr;
 }
 
+// Fused LM head + cross-entropy (Alg. 3).  Sizes are validated on the host; the workspace is carved up there.
+struct LmHeadParams {
+  int32_t n_tokens, d_model, vocab, tile_tokens;
+  int32_t v_pad;        // vocab rounded up to 256: row length of the two workspace matrices
+  float grad_scale;
+  const __bf16* h;      // [n_tokens][ld_h]
+  const __bf16* w;      // [vocab][ld_w]
+  int64_t ld_h, ld_w;
+  const int64_t* y;
+  float* loss;
+  float* lse;           // may be nullptr
+  void* dh;             // may be nullptr
+  int32_t dh_is_f32;
+  int64_t ld_dh;
+  float* dw;            // may be nullptr
+  int64_t ld_dw;
+  int32_t acc_dw;
+  float* logits;        // workspace [tile_tokens][v_pad]
+  __bf16* dlogits;      // workspace [tile_tokens][v_pad]
+  float2* part;         // workspace [v_pad / 128][tile_tokens]: (max, sum of exp) over 128 words
+};
+int64_t lm_head_workspace_bytes(int64_t tile_tokens, int64_t vocab);
+hipError_t launch_lm_head_loss(const LmHeadParams& p, hipStream_t stream);
+
 hipError_t launch_step_fwd(const FwdParams& p, hipStream_t stream);
 hipError_t launch_step_bwd(const BwdParams& p, hipStream_t stream);
 hipError_t launch_lse_merge(const MergeParams& p, hipStream_t stream);

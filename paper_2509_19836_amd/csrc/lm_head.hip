@@ -1,0 +1,373 @@
+// Sequence-level fusion of the LM head and the loss function (Sec. 3.3, Eq. 9, Alg. 3).
+//
+// Per sequence tile of B_s tokens, four launches:
+//   1. lm_logits_kernel       Logits^T tile = W_head H_i^T on the matrix cores (bf16 in, fp32 out).
+//                             Computed transposed so that a lane owns a token: the per-token
+//                             (max, sum of exp) over the wave's 128 words is a reduction over the
+//                             lane's own registers, as in the attention forward.  The fp32 logits of
+//                             the tile go to the workspace (the algorithm keeps them between its two
+//                             sweeps over the vocabulary); the partial (max, sum) pairs go to a side array.
+//   2. lm_loss_dlogits_kernel one work-group per token: merges the partial pairs into Lse_i, writes
+//                             the loss, then streams the token's logits once and writes
+//                             grad_scale * (exp(Logits - Lse) - E) as bf16 (HBM-bound).
+//   3. lm_dh_kernel           dH_i  = dLogits W_head          (contraction over the vocabulary)
+//   4. lm_dw_kernel           dW   += dLogits^T H_i           (contraction over the tile's tokens)
+// The three GEMMs share one main loop: 256 x 256 output tile per work-group of 8 waves (wave tile
+// 128 x 64, 128 accumulator registers), k-tiles of 64 double-buffered in LDS, operands read from LDS
+// either row-wise (the matrix is stored with the contraction index contiguous) or column-wise with
+// the transposing LDS read (the contraction index is the storage row), so no operand is ever
+// transposed in memory.
+#include <type_traits>
+
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace burst {
+
+namespace {
+
+constexpr int kLmThreads = 512;
+using LmRowsStager = TileStager<64, 256, kLmThreads>;    // storage [256 rows][64 k]
+using LmColsStager = TileStager<256, 64, kLmThreads, true>;   // storage [64 k][256 columns]; k in the row-wise operand's order
+constexpr int kLmRowsBytes = 256 * LmRowsStager::PITCH;
+constexpr int kLmColsBytes = 64 * LmColsStager::PITCH;
+
+// One GEMM operand: where its k-tiles come from and how they are staged.
+//   COLS = false: storage [x][k], k contiguous; the tile is rows x0 .. x0+255, columns k0 .. k0+63.
+//                 lim = number of valid storage rows (rows beyond are read as the last valid row).
+//   COLS = true : storage [k][x], x contiguous; the tile is rows k0 .. k0+63, columns x0 .. x0+255
+//                 (always inside the row).  lim = number of valid k rows (clamped the same way).
+template <bool COLS>
+struct LmOperand {
+  using Stager = std::conditional_t<COLS, LmColsStager, LmRowsStager>;
+  static constexpr int BYTES = COLS ? kLmColsBytes : kLmRowsBytes;
+  Stager st;
+  const __bf16* base;
+  const char* tile;
+  int64_t ld, step;
+  int lim, x0, k0;
+
+  __device__ __forceinline__ void init(const __bf16* ptr, int64_t ld_, int lim_, int x0_, int tid) {
+    ld = ld_;
+    lim = lim_;
+    x0 = x0_;
+    k0 = 0;
+    base = COLS ? ptr + x0 : ptr;
+    tile = reinterpret_cast<const char*>(COLS ? ptr + x0 : ptr + (int64_t)x0 * ld);
+    step = COLS ? 64 * ld * 2 : 128;
+    st.init(ld, tid);
+  }
+  __device__ __forceinline__ void issue(int tid) {
+    if (COLS) {
+      if (k0 + 64 <= lim) st.load_at(tile);
+      else st.load(base, ld, k0, lim, tid);
+    } else {
+      if (x0 + 256 <= lim) st.load_at(tile);
+      else st.load(base + k0, ld, x0, lim, tid);
+    }
+    tile += step;
+    k0 += 64;
+  }
+  __device__ __forceinline__ void commit(char* lds) const { st.store(lds); }
+  // fragment for the 16-wide k-step ks of the tile in LDS: lane -> row / column x_off + (lane & 31)
+  static __device__ __forceinline__ bf16x8 frag(const char* lds, int x_off, int ks, int lane) {
+    if (COLS) return lds_cols_operand<LmColsStager::PITCH>(lds, ks * 16, x_off, lane);
+    return lds_rows_operand<LmRowsStager::PITCH>(lds, x_off, ks * 16, lane & 31, lane >> 5);
+  }
+};
+
+template <bool A_COLS, bool B_COLS>
+struct LmGemm {
+  using OpA = LmOperand<A_COLS>;
+  using OpB = LmOperand<B_COLS>;
+  static constexpr int STAGE = OpA::BYTES + OpB::BYTES;
+  static constexpr int LDS = 2 * STAGE;
+
+  // acc[mb][nb]: rows 32 mb + ... of the wave's 128, columns 32 nb + ... of its 64.  nk >= 1.
+  static __device__ __forceinline__ void run(f32x16 (&acc)[4][2], char* smem, OpA& a, OpB& b, int nk, int wm, int wn,
+                                             int tid, int lane) {
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
+    a.issue(tid);
+    b.issue(tid);
+    a.commit(smem);
+    b.commit(smem + OpA::BYTES);
+    __syncthreads();
+    int buf = 0;
+    for (int kt = 0; kt < nk; ++kt) {
+      const bool more = kt + 1 < nk;
+      if (more) {
+        a.issue(tid);
+        b.issue(tid);
+      }
+      const char* at = smem + buf * STAGE;
+      const char* bt = at + OpA::BYTES;
+      bf16x8 af[2][4], bf[2][2];
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb) af[0][mb] = OpA::frag(at, wm * 128 + 32 * mb, 0, lane);
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) bf[0][nb] = OpB::frag(bt, wn * 64 + 32 * nb, 0, lane);
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        if (ks + 1 < 4) {
+#pragma unroll
+          for (int mb = 0; mb < 4; ++mb) af[(ks + 1) & 1][mb] = OpA::frag(at, wm * 128 + 32 * mb, ks + 1, lane);
+#pragma unroll
+          for (int nb = 0; nb < 2; ++nb) bf[(ks + 1) & 1][nb] = OpB::frag(bt, wn * 64 + 32 * nb, ks + 1, lane);
+        }
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+          for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mfma32(af[ks & 1][mb], bf[ks & 1][nb], acc[mb][nb]);
+      }
+      if (more) {
+        a.commit(smem + (buf ^ 1) * STAGE);
+        b.commit(smem + (buf ^ 1) * STAGE + OpA::BYTES);
+      }
+      __syncthreads();
+      buf ^= 1;
+    }
+  }
+};
+
+// Work-group -> output tile.  Work-group n runs on XCD n mod 8; each XCD takes groups of 4 x 8
+// tiles (one per CU), so the 32 work-groups that share an L2 at a time read 4 + 8 operand panels.
+__device__ __forceinline__ bool lm_tile(int bid, int TM, int TN, int& tm, int& tn) {
+  const int groups_m = (TM + 3) / 4, groups_n = (TN + 7) / 8;
+  const int xcd = bid & 7, slot = bid >> 3;
+  const int group = (slot >> 5) * 8 + xcd, within = slot & 31;
+  if (group >= groups_m * groups_n) return false;
+  const int gm = group % groups_m, gn = group / groups_m;
+  tm = gm * 4 + (within & 3);
+  tn = gn * 8 + (within >> 2);
+  return tm < TM && tn < TN;
+}
+int lm_grid(int TM, int TN) {
+  const int groups = ((TM + 3) / 4) * ((TN + 7) / 8);
+  return (groups + 7) / 8 * 8 * 32;
+}
+
+// (max, sum of exp(x - max)) pairs combine like the log-sum-exp merge of the attention forward.
+__device__ __forceinline__ void lm_combine(float& m, float& l, float m2, float l2) {
+  const float mm = fmaxf(m, m2);
+  l = (mm == -INFINITY) ? 0.f : l * __expf(m - mm) + l2 * __expf(m2 - mm);
+  m = mm;
+}
+
+// ---------------------------------------------------------------------------------------------
+// 1. Logits^T tile (rows: words, columns: tokens of the sequence tile), Alg. 3 forward sweep.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kLmThreads, 1) void lm_logits_kernel(LmHeadParams p, int s0, int n_rows, int TM, int TN) {
+  using G = LmGemm<false, false>;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  int tm, tn;
+  if (!lm_tile(blockIdx.x, TM, TN, tm, tn)) return;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave & 1, wn = wave >> 1;
+  const int m0 = tm * 256, n0 = tn * 256;
+  G::OpA a;
+  G::OpB b;
+  a.init(p.w, p.ld_w, p.vocab, m0, tid);
+  b.init(p.h + (int64_t)s0 * p.ld_h, p.ld_h, n_rows, n0, tid);
+  f32x16 acc[4][2];
+  G::run(acc, smem, a, b, p.d_model / 64, wm, wn, tid, lane);
+
+  const int word0 = m0 + wm * 128;                 // first word of the wave
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+    const int token = n0 + wn * 64 + 32 * nb + r;  // < tile_tokens: the tile count covers n_rows only
+    float* dst = p.logits + (int64_t)token * p.v_pad + word0 + 4 * h;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        f32x4 x = {acc[mb][nb][4 * g], acc[mb][nb][4 * g + 1], acc[mb][nb][4 * g + 2], acc[mb][nb][4 * g + 3]};
+        *reinterpret_cast<f32x4*>(dst + 32 * mb + 8 * g) = x;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const bool real = word0 + 32 * mb + 8 * g + 4 * h + j < p.vocab;   // padding words stay out of Lse
+          acc[mb][nb][4 * g + j] = real ? x[j] : -INFINITY;
+          mx = fmaxf(mx, acc[mb][nb][4 * g + j]);
+        }
+      }
+    mx = fmaxf(mx, half_swap(mx));
+    float sum = 0.f;
+    if (mx != -INFINITY) {
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sum += __expf(acc[mb][nb][v] - mx);
+    }
+    sum += half_swap(sum);
+    if (h == 0) p.part[(int64_t)(tm * 2 + wm) * p.tile_tokens + token] = float2{mx, sum};
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// 2. Lse_i, loss_i and dLogits of one token per work-group (Alg. 3: the loss line and the first
+//    two lines of the backward sweep).  Rows n_rows .. gridDim.x-1 are zero-filled: they pad the
+//    contraction of the dW GEMM.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void lm_loss_dlogits_kernel(LmHeadParams p, int s0, int n_rows, int want_grad) {
+  __shared__ float red_m[4], red_l[4];
+  const int i = blockIdx.x, tid = threadIdx.x;
+  __bf16* drow = p.dlogits + (int64_t)i * p.v_pad;
+  const bf16x8 zero8 = {(__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f};
+  if (i >= n_rows) {
+    for (int j = tid * 8; j < p.v_pad; j += 2048) *reinterpret_cast<bf16x8*>(drow + j) = zero8;
+    return;
+  }
+  float m = -INFINITY, l = 0.f;
+  const int n_part = p.v_pad / 128;
+  for (int pp = tid; pp < n_part; pp += 256) {
+    const float2 x = p.part[(int64_t)pp * p.tile_tokens + i];
+    lm_combine(m, l, x.x, x.y);
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) lm_combine(m, l, __shfl_xor(m, off), __shfl_xor(l, off));
+  if ((tid & 63) == 0) {
+    red_m[tid >> 6] = m;
+    red_l[tid >> 6] = l;
+  }
+  __syncthreads();
+  m = red_m[0];
+  l = red_l[0];
+#pragma unroll
+  for (int w = 1; w < 4; ++w) lm_combine(m, l, red_m[w], red_l[w]);
+  const float lse = m + __logf(l);
+  const int64_t y = p.y[s0 + i];
+  const bool ok = y >= 0 && y < p.vocab;
+  const float* lrow = p.logits + (int64_t)i * p.v_pad;
+  if (tid == 0) {
+    p.loss[s0 + i] = ok ? lse - lrow[ok ? y : 0] : 0.f;
+    if (p.lse) p.lse[s0 + i] = lse;
+  }
+  if (!want_grad) return;
+  if (!ok) {
+    for (int j = tid * 8; j < p.v_pad; j += 2048) *reinterpret_cast<bf16x8*>(drow + j) = zero8;
+    return;
+  }
+  const int yi = (int)y;
+  const float gs = p.grad_scale;
+  for (int j = tid * 8; j < p.v_pad; j += 2048) {
+    const f32x4 x0 = *reinterpret_cast<const f32x4*>(lrow + j), x1 = *reinterpret_cast<const f32x4*>(lrow + j + 4);
+    bf16x8 out;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float x = e < 4 ? x0[e] : x1[e - 4];
+      const float g = gs * (__expf(x - lse) - (j + e == yi ? 1.f : 0.f));
+      out[e] = (__bf16)(j + e < p.vocab ? g : 0.f);
+    }
+    *reinterpret_cast<bf16x8*>(drow + j) = out;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// 3. dH_i = dLogits W_head (rows: tokens, columns: hidden, contraction: words).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kLmThreads, 1) void lm_dh_kernel(LmHeadParams p, int s0, int n_rows, int TM, int TN) {
+  using G = LmGemm<false, true>;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  int tm, tn;
+  if (!lm_tile(blockIdx.x, TM, TN, tm, tn)) return;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave & 1, wn = wave >> 1;
+  const int m0 = tm * 256, n0 = tn * 256;
+  G::OpA a;
+  G::OpB b;
+  a.init(p.dlogits, p.v_pad, p.tile_tokens, m0, tid);
+  b.init(p.w, p.ld_w, p.vocab, n0, tid);
+  f32x16 acc[4][2];
+  G::run(acc, smem, a, b, (p.vocab + 63) / 64, wm, wn, tid, lane);   // dLogits is zero beyond the vocabulary
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = m0 + wm * 128 + 32 * mb + 8 * (v >> 2) + 4 * h + (v & 3);
+      if (row >= n_rows) continue;
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        const int64_t off = (int64_t)(s0 + row) * p.ld_dh + n0 + wn * 64 + 32 * nb + r;
+        if (p.dh_is_f32) ((float*)p.dh)[off] = acc[mb][nb][v];
+        else ((__bf16*)p.dh)[off] = (__bf16)acc[mb][nb][v];
+      }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// 4. dW (+)= dLogits^T H_i (rows: words, columns: hidden, contraction: tokens of the tile).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kLmThreads, 1) void lm_dw_kernel(LmHeadParams p, int s0, int n_rows, int TM, int TN, int accumulate) {
+  using G = LmGemm<true, true>;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  int tm, tn;
+  if (!lm_tile(blockIdx.x, TM, TN, tm, tn)) return;
+  const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave & 1, wn = wave >> 1;
+  const int m0 = tm * 256, n0 = tn * 256;
+  G::OpA a;
+  G::OpB b;
+  a.init(p.dlogits, p.v_pad, p.tile_tokens, m0, tid);
+  b.init(p.h + (int64_t)s0 * p.ld_h, p.ld_h, n_rows, n0, tid);
+  f32x16 acc[4][2];
+  G::run(acc, smem, a, b, (n_rows + 63) / 64, wm, wn, tid, lane);    // dLogits rows beyond n_rows are zero
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = m0 + wm * 128 + 32 * mb + 8 * (v >> 2) + 4 * h + (v & 3);
+      if (row >= p.vocab) continue;
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        float* dst = p.dw + (int64_t)row * p.ld_dw + n0 + wn * 64 + 32 * nb + r;
+        *dst = accumulate ? *dst + acc[mb][nb][v] : acc[mb][nb][v];
+      }
+    }
+}
+
+__global__ __launch_bounds__(256) void lm_zero_dw_kernel(LmHeadParams p) {
+  const int d4 = p.d_model / 4;
+  const int64_t total = (int64_t)p.vocab * d4;
+  for (int64_t i = blockIdx.x * 256ll + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256)
+    *reinterpret_cast<f32x4*>(p.dw + (i / d4) * p.ld_dw + (i % d4) * 4) = f32x4{0.f, 0.f, 0.f, 0.f};
+}
+
+}  // namespace
+
+int64_t lm_head_workspace_bytes(int64_t tile_tokens, int64_t vocab) {
+  const int64_t v_pad = (vocab + 255) / 256 * 256;
+  return tile_tokens * v_pad * 4 + tile_tokens * v_pad * 2 + (v_pad / 128) * tile_tokens * 8;
+}
+
+hipError_t launch_lm_head_loss(const LmHeadParams& p, hipStream_t stream) {
+  const int want_grad = (p.dh || p.dw) ? 1 : 0;
+  const int TD = p.d_model / 256, TV = p.v_pad / 256;
+  constexpr int kLdsLogits = LmGemm<false, false>::LDS, kLdsDh = LmGemm<false, true>::LDS, kLdsDw = LmGemm<true, true>::LDS;
+  if (p.n_tokens == 0 && p.dw && !p.acc_dw) {
+    hipLaunchKernelGGL(lm_zero_dw_kernel, dim3(2048), dim3(256), 0, stream, p);
+    return hipGetLastError();
+  }
+  for (int s0 = 0; s0 < p.n_tokens; s0 += p.tile_tokens) {
+    const int n_rows = p.n_tokens - s0 < p.tile_tokens ? p.n_tokens - s0 : p.tile_tokens;
+    const int TT = (n_rows + 255) / 256, k_rows = (n_rows + 63) / 64 * 64;
+    hipLaunchKernelGGL(lm_logits_kernel, dim3(lm_grid(TV, TT)), dim3(kLmThreads), kLdsLogits, stream, p, s0,
+                       n_rows, TV, TT);
+    hipLaunchKernelGGL(lm_loss_dlogits_kernel, dim3(want_grad ? k_rows : n_rows), dim3(256), 0, stream, p, s0, n_rows, want_grad);
+    if (p.dh)
+      hipLaunchKernelGGL(lm_dh_kernel, dim3(lm_grid(TT, TD)), dim3(kLmThreads), kLdsDh, stream, p, s0, n_rows,
+                         TT, TD);
+    if (p.dw)
+      hipLaunchKernelGGL(lm_dw_kernel, dim3(lm_grid(TV, TD)), dim3(kLmThreads), kLdsDw, stream, p, s0, n_rows,
+                         TV, TD, (p.acc_dw || s0 > 0) ? 1 : 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+}  // namespace burst

@@ -123,3 +123,15 @@ def local_block_mask(pattern, pos_q, pos_k, block_rows):
         if pos.size % block_rows or not np.array_equal(first, last):
             raise ValueError("local row blocks straddle global blocks")
     return np.ascontiguousarray(pattern[np.ix_(pos_q[::block_rows] // block_rows, pos_k[::block_rows] // block_rows)])
+
+
+def lm_head_tensors(seed, n_tokens, d_model, vocab, ignored=0):
+    """Seeded inputs of the fused LM head + loss: H_last ~ N(0, 1) and W_head ~ N(0, 4/d) as bfloat16
+    bit patterns (logits of standard deviation about 2, the spread of a trained head's logits), targets
+    uniform over the vocabulary, the first `ignored` of them set to -100 (tokens without a loss)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    H = f32_to_bf16_bits(rng.standard_normal((n_tokens, d_model), dtype=np.float32))
+    W = f32_to_bf16_bits(rng.standard_normal((vocab, d_model), dtype=np.float32) * np.float32(2.0 / np.sqrt(d_model)))
+    Y = rng.integers(0, vocab, n_tokens, dtype=np.int64)
+    Y[:ignored] = -100
+    return H, W, Y

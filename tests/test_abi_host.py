@@ -15,10 +15,11 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol(lib):
-    header = open(os.path.join(ROOT, "include", "burst_attn.h")).read()
-    declared = set(re.findall(r"\b(burst_attn_\w+)\s*\(", header))
+    header = "".join(open(os.path.join(ROOT, "include", f)).read() for f in sorted(os.listdir(os.path.join(ROOT, "include")))
+                     if f.endswith(".h"))
+    declared = set(re.findall(r"\b(burst_(?:attn|lm_head)_\w+)\s*\(", header))
     assert {"burst_attn_step_fwd", "burst_attn_lse_merge", "burst_attn_step_bwd",
-            "burst_attn_preprocess_bwd"} <= declared
+            "burst_attn_preprocess_bwd", "burst_lm_head_loss"} <= declared
     raw = lib.raw()
     for name in sorted(declared):
         assert hasattr(raw, name), f"{name} declared in the header but not exported"
@@ -32,6 +33,7 @@ def test_struct_layouts_match_the_header(lib):
     assert C.sizeof(lib.burst_tensor_t) == 40
     assert C.sizeof(lib.burst_rowvec_t) == 24
     assert C.sizeof(lib.burst_mask_t) == 16 + 32 + 32 + 32
+    assert C.sizeof(lib.burst_lm_head_shape_t) == 40
 
 
 @pytest.mark.parametrize("G,N", [(1, 8), (2, 24), (4, 64), (8, 128)])
@@ -329,3 +331,31 @@ def test_block_pattern_slices_and_pair_counts(lib):
     with pytest.raises(ValueError):   # striped rows do not form blocks of consecutive tokens
         m = ring.fill_mask("striped", 0, 1, G, N)
         wl.local_block_mask(pattern, ring.mask_positions(m, "q"), ring.mask_positions(m, "k"), R)
+
+
+def test_lm_head_arguments_are_checked_on_the_host(lib):
+    """Validation of the fused LM head + loss call: nothing here reaches a launch; the pointers are
+    made-up numbers that are never dereferenced."""
+    raw = lib.raw()
+    INV, UNS = lib.BURST_ERR_INVALID_ARG, lib.BURST_ERR_UNSUPPORTED
+    ok = lib.lm_head_shape(1000, 512, 3000, 256)
+    need = lib.burst_lm_head_workspace_bytes(ok)
+    v_pad = 3072
+    assert need == 256 * v_pad * 4 + 256 * v_pad * 2 + (v_pad // 128) * 256 * 8
+    for bad in (lib.lm_head_shape(-1, 512, 3000, 256), lib.lm_head_shape(10, 512, 0, 256),
+                lib.lm_head_shape(10, 512, 3000, 100), lib.lm_head_shape(10, 512, 3000, 0),
+                lib.lm_head_shape(10, 0, 3000, 256), lib.lm_head_shape(10, 512, 3000, 256, float("inf"))):
+        assert raw.burst_lm_head_workspace_bytes(C.byref(bad)) == -1
+
+    def call(shape=ok, h=0x10000, ld_h=512, w=0x20000, ld_w=512, y=0x30000, loss=0x40000, lse=None, dh=0x50000,
+             dh_dtype=1, ld_dh=512, dw=0x60000, ld_dw=512, ws=0x70000, ws_bytes=need):
+        return raw.burst_lm_head_loss(C.byref(shape) if shape is not None else None, h, ld_h, w, ld_w, y, loss, lse, dh,
+                                      dh_dtype, ld_dh, dw, ld_dw, 0, ws, ws_bytes, None)
+    assert call(shape=None) == INV
+    assert call(shape=lib.lm_head_shape(1000, 500, 3000, 256)) == UNS      # d not a multiple of 256
+    assert call(shape=lib.lm_head_shape(1000, 512, 1 << 23, 256)) == UNS   # vocabulary beyond the 32-bit tile offsets
+    assert call(h=None) == INV and call(w=None) == INV and call(y=None) == INV and call(loss=None) == INV
+    assert call(h=0x10008) == INV                                          # misaligned
+    assert call(ld_h=504) == INV and call(ld_w=511) == INV                 # leading dimension below d / not a multiple of 8
+    assert call(dh_dtype=7) == INV and call(ld_dh=256) == INV and call(ld_dw=510) == INV
+    assert call(ws=None) == INV and call(ws=0x70010) == INV and call(ws_bytes=need - 1) == INV
