@@ -88,6 +88,82 @@ def cpu_baseline(w, kind, dev_i, shards, sample_rows, seed, window=0, pattern=No
                       f"+ D + backward step per shard in fp64 numpy; {pairs} visible pairs"}
 
 
+def lm_head_bench(args):
+    """The second kernel family (fused LM head + cross-entropy, Alg. 3) on the per-device share of a
+    128K-token sequence over 8 devices with a LLaMA-7B-sized head.  Not the headline metric: run with
+    --lm-head.  One step = one burst_lm_head_loss call (forward and backward of every sequence tile)."""
+    import numpy as np
+    import torch
+    from paper_2509_19836_amd import binding as lib, workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    N, d, v, B_s = args.lm_tokens, 4096, args.vocab, args.tile_tokens
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(wl.BASE_SEED + 900)
+    h = torch.randn(N, d, device="cuda", generator=gen).to(torch.bfloat16)
+    w = (torch.randn(v, d, device="cuda", generator=gen) * (2.0 / d ** 0.5)).to(torch.bfloat16)
+    y = torch.randint(0, v, (N,), device="cuda", generator=gen)
+    loss = torch.empty(N, device="cuda", dtype=torch.float32)
+    dh = torch.empty(N, d, device="cuda", dtype=torch.bfloat16)
+    dw = torch.zeros(v, d, device="cuda", dtype=torch.float32)
+    shp = lib.lm_head_shape(N, d, v, B_s, 1.0 / N)
+    ws = torch.empty(lib.burst_lm_head_workspace_bytes(shp), dtype=torch.uint8, device="cuda")
+    full = lambda: lib.burst_lm_head_loss(shp, h, w, y, loss, ws, d_h=dh, d_w=dw, accumulate_dw=True)
+    fwd_only = lambda: lib.burst_lm_head_loss(shp, h, w, y, loss, ws)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps):
+        a, b = ev(), ev()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps, (time.perf_counter() - t0) / reps * 1e3
+    for _ in range(args.warmup):
+        full()
+    ms, wall_ms = timed(full, args.steps)
+    fwd_ms, _ = timed(fwd_only, args.steps)
+    flops = 6.0 * N * d * v
+    value = flops / (wall_ms * 1e-3) / 1e12
+    out = {
+        "metric": "LM head + cross-entropy fwd+bwd TFLOPS (6 N d v)", "value": round(value, 2), "unit": "TFLOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"fused LM head + loss (Alg. 3): {N} tokens (a 128K sequence over 8 devices), d={d}, "
+                               f"vocabulary {v}, sequence tiles of {B_s} tokens, dH bf16, dW fp32 accumulated",
+                   "workspace_gib": round(ws.numel() / 2 ** 30, 3)},
+        "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
+        "forward_only_ms": round(fwd_ms, 3),
+        "forward_only_tflops": round(2.0 * N * d * v / (fwd_ms * 1e-3) / 1e12, 2),
+        "mean_loss": round(float(loss.mean()), 4),
+        # the three GEMM kernels carry all the flops; the call also holds the HBM-bound per-token kernel,
+        # so this is a lower bound of what the GEMM kernels reach (per-kernel times: profiles/)
+        "roofline": {"bound": "mfma", "kernel": "lm_logits_kernel + lm_dh_kernel + lm_dw_kernel (whole call)",
+                     "achieved": round(flops / (ms * 1e-3) / 1e12, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4), "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import lm_head_oracle as lmo
+        n_s = 4096
+        Hb, Wb, Y = wl.lm_head_tensors(wl.BASE_SEED + 901, n_s, d, v)
+        H64, W64 = wl.bf16_bits_to_f64(Hb), wl.bf16_bits_to_f64(Wb)
+        t0 = time.perf_counter()
+        lmo.lm_head_loss(H64, W64, Y, 1.0 / n_s)
+        dt = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p_.get("num_threads", 1) for p_ in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        out["cpu_baseline"] = {"value": 6.0 * n_s * d * v / dt / 1e12, "unit": "TFLOPS", "cores": int(cores),
+                               "kind": "oracle", "seconds": round(dt, 3),
+                               "sample": f"{n_s} tokens against the whole {v}-word head, definition in fp64 numpy"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,11 +182,17 @@ def main():
     ap.add_argument("--block-rows", type=int, default=512, help="rows of a (square) block of that pattern")
     ap.add_argument("--cpu-shards", type=int, default=4, help="KV shards the CPU baseline sample covers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--lm-head", action="store_true", help="measure the fused LM head + loss (Alg. 3) instead of the ring")
+    ap.add_argument("--lm-tokens", type=int, default=16384)
+    ap.add_argument("--vocab", type=int, default=32000, help="--lm-head: vocabulary (32000: LLaMA-1/2, 128256: LLaMA-3)")
+    ap.add_argument("--tile-tokens", type=int, default=8192, help="--lm-head: tokens per sequence tile (B_s)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build measures the per-device compute step on ONE GPU; the ring is simulated "
                  "in HBM and there is no multi-GPU path (--gpus must be 1)")
 
+    if args.lm_head:
+        return lm_head_bench(args)
     import torch
     from paper_2509_19836_amd import binding as lib, ring, workloads as wl
     assert torch.cuda.is_available(), "bench.py needs the GPU"

@@ -37,8 +37,8 @@ typedef struct {
   int32_t _pad;
 } burst_lm_head_shape_t;
 
-/* Bytes of workspace burst_lm_head_loss needs for this shape (a function of tile_tokens and vocab
- * only), or -1 for an invalid shape.  Host only. */
+/* Bytes of workspace burst_lm_head_loss needs for this shape (n_tokens and grad_scale play no
+ * part), or -1 for an invalid shape.  Host only. */
 int64_t burst_lm_head_workspace_bytes(const burst_lm_head_shape_t* shape);
 
 /*

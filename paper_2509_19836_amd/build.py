@@ -43,7 +43,8 @@ def build(verbose=False, extra_flags=(), out_path=None, tag=""):
         out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
         if pr.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
-        check_resources(out, src)
+        if not os.environ.get("BURST_ALLOW_SPILLS"):   # experiments only: the committed build must not spill
+            check_resources(out, src)
         if verbose and out.strip():
             print(out)
         objs.append(obj)

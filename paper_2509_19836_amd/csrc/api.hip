@@ -400,7 +400,7 @@ static int check_lm_shape(const burst_lm_head_shape_t* s) {
 
 int64_t burst_lm_head_workspace_bytes(const burst_lm_head_shape_t* shape) {
   if (check_lm_shape(shape) != BURST_OK) return -1;
-  return lm_head_workspace_bytes(shape->tile_tokens, shape->vocab);
+  return lm_head_workspace_bytes(shape->tile_tokens, shape->vocab, shape->d_model);
 }
 
 int burst_lm_head_loss(const burst_lm_head_shape_t* shape, const void* h_last, int64_t ld_h, const void* w_head,
@@ -424,7 +424,7 @@ int burst_lm_head_loss(const burst_lm_head_shape_t* shape, const void* h_last, i
     if (!aligned(d_w, 16) || ld_dw < d || ld_dw % 4 != 0) return BURST_ERR_INVALID_ARG;
     if (ld_dw > max_ld) return BURST_ERR_UNSUPPORTED;
   }
-  if (!aligned(workspace, 256) || workspace_bytes < lm_head_workspace_bytes(shape->tile_tokens, shape->vocab))
+  if (!aligned(workspace, 256) || workspace_bytes < lm_head_workspace_bytes(shape->tile_tokens, shape->vocab, shape->d_model))
     return BURST_ERR_INVALID_ARG;
   LmHeadParams p;
   std::memset(&p, 0, sizeof(p));
@@ -452,6 +452,7 @@ int burst_lm_head_loss(const burst_lm_head_shape_t* shape, const void* h_last, i
   p.logits = (float*)ws;
   p.dlogits = (__bf16*)(ws + cells * 4);
   p.part = (float2*)(ws + cells * 6);
+  p.ht = (__bf16*)(ws + cells * 6 + (int64_t)(p.v_pad / 128) * p.tile_tokens * 8);
   hipError_t e = launch_lm_head_loss(p, (hipStream_t)hip_stream);
   return e == hipSuccess ? BURST_OK : hip_fail(e);
 }

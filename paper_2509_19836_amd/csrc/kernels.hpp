@@ -99,8 +99,9 @@ struct LmHeadParams {
   float* logits;        // workspace [tile_tokens][v_pad]
   __bf16* dlogits;      // workspace [tile_tokens][v_pad]
   float2* part;         // workspace [v_pad / 128][tile_tokens]: (max, sum of exp) over 128 words
+  __bf16* ht;           // workspace [d_model][tile_tokens]: the sequence tile's rows of h, transposed
 };
-int64_t lm_head_workspace_bytes(int64_t tile_tokens, int64_t vocab);
+int64_t lm_head_workspace_bytes(int64_t tile_tokens, int64_t vocab, int64_t d_model);
 hipError_t launch_lm_head_loss(const LmHeadParams& p, hipStream_t stream);
 
 hipError_t launch_step_fwd(const FwdParams& p, hipStream_t stream);

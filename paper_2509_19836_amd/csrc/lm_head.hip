@@ -11,12 +11,15 @@
 //                             the loss, then streams the token's logits once and writes
 //                             grad_scale * (exp(Logits - Lse) - E) as bf16 (HBM-bound).
 //   3. lm_dh_kernel           dH_i  = dLogits W_head          (contraction over the vocabulary)
-//   4. lm_dw_kernel           dW   += dLogits^T H_i           (contraction over the tile's tokens)
+//   4. lm_transpose_h_kernel + lm_dw_kernel
+//                             dW^T += H_i^T dLogits           (contraction over the tile's tokens)
 // The three GEMMs share one main loop: 256 x 256 output tile per work-group of 8 waves (wave tile
 // 128 x 64, 128 accumulator registers), k-tiles of 64 double-buffered in LDS, operands read from LDS
 // either row-wise (the matrix is stored with the contraction index contiguous) or column-wise with
-// the transposing LDS read (the contraction index is the storage row), so no operand is ever
-// transposed in memory.
+// the transposing LDS read (the contraction index is the storage row).  Only H_i, a few MB per
+// sequence tile, is ever transposed in memory.  The main loop is bound by LDS traffic as much as by
+// the matrix pipe (0.75 KB of operand reads per MFMA plus the staging writes against 128 B/clk),
+// which is why the wave tile is as large as 128 accumulator registers allow.
 #include <type_traits>
 
 #include "common.hpp"
@@ -26,21 +29,35 @@ namespace burst {
 
 namespace {
 
-constexpr int kLmThreads = 512;
-using LmRowsStager = TileStager<64, 256, kLmThreads>;    // storage [256 rows][64 k]
-using LmColsStager = TileStager<256, 64, kLmThreads, true>;   // storage [64 k][256 columns]; k in the row-wise operand's order
-constexpr int kLmRowsBytes = 256 * LmRowsStager::PITCH;
-constexpr int kLmColsBytes = 64 * LmColsStager::PITCH;
+// Output tile of a work-group: 256 x kLmBN, k-tiles of kLmBK, one wave per 128 x 64 sub-tile
+// (128 accumulator registers).  With kLmBN = 128 a work-group is 4 waves and two of them share a
+// CU (two waves per SIMD, from different work-groups): while one waits at its barrier or for its
+// staging loads, the other one's MFMAs keep the matrix pipe busy.
+#ifndef LM_BN
+#define LM_BN 256
+#endif
+#ifndef LM_BK
+#define LM_BK 64
+#endif
+#ifndef LM_WN
+#define LM_WN 64
+#endif
+constexpr int kLmBM = 256, kLmBN = LM_BN, kLmBK = LM_BK, kLmKS = kLmBK / 16, kLmWN = LM_WN, kLmNB = kLmWN / 32;
+constexpr int kLmWaves = (kLmBM / 128) * (kLmBN / kLmWN), kLmThreads = 64 * kLmWaves;
+constexpr int kLmPerCU = kLmWN == 128 ? 1 : 512 / kLmThreads;
 
-// One GEMM operand: where its k-tiles come from and how they are staged.
-//   COLS = false: storage [x][k], k contiguous; the tile is rows x0 .. x0+255, columns k0 .. k0+63.
+// One GEMM operand: where its k-tiles come from and how they are staged.  X: extent of the tile
+// along the operand's own (non-contracted) index.
+//   COLS = false: storage [x][k], k contiguous; the tile is rows x0 .. x0+X-1, columns k0 .. k0+BK-1.
 //                 lim = number of valid storage rows (rows beyond are read as the last valid row).
-//   COLS = true : storage [k][x], x contiguous; the tile is rows k0 .. k0+63, columns x0 .. x0+255
-//                 (always inside the row).  lim = number of valid k rows (clamped the same way).
-template <bool COLS>
+//   COLS = true : storage [k][x], x contiguous; the tile is rows k0 .. k0+BK-1, columns x0 .. x0+X-1
+//                 (always inside the row), its rows permuted in LDS so that the column-wise read
+//                 hands out k in the row-wise operand's order.  lim = number of valid k rows
+//                 (clamped the same way).
+template <bool COLS, int X>
 struct LmOperand {
-  using Stager = std::conditional_t<COLS, LmColsStager, LmRowsStager>;
-  static constexpr int BYTES = COLS ? kLmColsBytes : kLmRowsBytes;
+  using Stager = std::conditional_t<COLS, TileStager<X, kLmBK, kLmThreads, true>, TileStager<kLmBK, X, kLmThreads>>;
+  static constexpr int BYTES = (COLS ? kLmBK : X) * Stager::PITCH;
   Stager st;
   const __bf16* base;
   const char* tile;
@@ -54,42 +71,44 @@ struct LmOperand {
     k0 = 0;
     base = COLS ? ptr + x0 : ptr;
     tile = reinterpret_cast<const char*>(COLS ? ptr + x0 : ptr + (int64_t)x0 * ld);
-    step = COLS ? 64 * ld * 2 : 128;
+    step = COLS ? kLmBK * ld * 2 : kLmBK * 2;
     st.init(ld, tid);
   }
-  __device__ __forceinline__ void issue(int tid) {
+  __device__ __forceinline__ void issue(int tid) {   // loads of the next k-tile
     if (COLS) {
-      if (k0 + 64 <= lim) st.load_at(tile);
+      if (k0 + kLmBK <= lim) st.load_at(tile);
       else st.load(base, ld, k0, lim, tid);
     } else {
-      if (x0 + 256 <= lim) st.load_at(tile);
+      if (x0 + X <= lim) st.load_at(tile);
       else st.load(base + k0, ld, x0, lim, tid);
     }
     tile += step;
-    k0 += 64;
+    k0 += kLmBK;
   }
   __device__ __forceinline__ void commit(char* lds) const { st.store(lds); }
   // fragment for the 16-wide k-step ks of the tile in LDS: lane -> row / column x_off + (lane & 31)
   static __device__ __forceinline__ bf16x8 frag(const char* lds, int x_off, int ks, int lane) {
-    if (COLS) return lds_cols_operand<LmColsStager::PITCH>(lds, ks * 16, x_off, lane);
-    return lds_rows_operand<LmRowsStager::PITCH>(lds, x_off, ks * 16, lane & 31, lane >> 5);
+    if (COLS) return lds_cols_operand<Stager::PITCH>(lds, ks * 16, x_off, lane);
+    return lds_rows_operand<Stager::PITCH>(lds, x_off, ks * 16, lane & 31, lane >> 5);
   }
 };
 
 template <bool A_COLS, bool B_COLS>
 struct LmGemm {
-  using OpA = LmOperand<A_COLS>;
-  using OpB = LmOperand<B_COLS>;
+  using OpA = LmOperand<A_COLS, kLmBM>;
+  using OpB = LmOperand<B_COLS, kLmBN>;
   static constexpr int STAGE = OpA::BYTES + OpB::BYTES;
   static constexpr int LDS = 2 * STAGE;
 
-  // acc[mb][nb]: rows 32 mb + ... of the wave's 128, columns 32 nb + ... of its 64.  nk >= 1.
-  static __device__ __forceinline__ void run(f32x16 (&acc)[4][2], char* smem, OpA& a, OpB& b, int nk, int wm, int wn,
+  // acc[mb][nb]: rows 32 mb + ... of the wave's 128, columns 32 nb + ... of its 64.  nk >= 1 k-tiles.
+  // The loads of k-tile t + 1 are issued before the MFMAs of tile t and written to the other LDS
+  // buffer after them; one barrier per k-tile.
+  static __device__ __forceinline__ void run(f32x16 (&acc)[4][kLmNB], char* smem, OpA& a, OpB& b, int nk, int wm, int wn,
                                              int tid, int lane) {
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
+      for (int nb = 0; nb < kLmNB; ++nb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
     a.issue(tid);
@@ -106,23 +125,23 @@ struct LmGemm {
       }
       const char* at = smem + buf * STAGE;
       const char* bt = at + OpA::BYTES;
-      bf16x8 af[2][4], bf[2][2];
+      bf16x8 af[2][4], bf[2][kLmNB];
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb) af[0][mb] = OpA::frag(at, wm * 128 + 32 * mb, 0, lane);
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) bf[0][nb] = OpB::frag(bt, wn * 64 + 32 * nb, 0, lane);
+      for (int nb = 0; nb < kLmNB; ++nb) bf[0][nb] = OpB::frag(bt, wn * kLmWN + 32 * nb, 0, lane);
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        if (ks + 1 < 4) {
+      for (int ks = 0; ks < kLmKS; ++ks) {
+        if (ks + 1 < kLmKS) {
 #pragma unroll
           for (int mb = 0; mb < 4; ++mb) af[(ks + 1) & 1][mb] = OpA::frag(at, wm * 128 + 32 * mb, ks + 1, lane);
 #pragma unroll
-          for (int nb = 0; nb < 2; ++nb) bf[(ks + 1) & 1][nb] = OpB::frag(bt, wn * 64 + 32 * nb, ks + 1, lane);
+          for (int nb = 0; nb < kLmNB; ++nb) bf[(ks + 1) & 1][nb] = OpB::frag(bt, wn * kLmWN + 32 * nb, ks + 1, lane);
         }
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-          for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mfma32(af[ks & 1][mb], bf[ks & 1][nb], acc[mb][nb]);
+          for (int nb = 0; nb < kLmNB; ++nb) acc[mb][nb] = mfma32(af[ks & 1][mb], bf[ks & 1][nb], acc[mb][nb]);
       }
       if (more) {
         a.commit(smem + (buf ^ 1) * STAGE);
@@ -161,25 +180,25 @@ __device__ __forceinline__ void lm_combine(float& m, float& l, float m2, float l
 // ---------------------------------------------------------------------------------------------
 // 1. Logits^T tile (rows: words, columns: tokens of the sequence tile), Alg. 3 forward sweep.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kLmThreads, 1) void lm_logits_kernel(LmHeadParams p, int s0, int n_rows, int TM, int TN) {
+__global__ __launch_bounds__(kLmThreads, kLmPerCU) void lm_logits_kernel(LmHeadParams p, int s0, int n_rows, int TM, int TN) {
   using G = LmGemm<false, false>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   int tm, tn;
   if (!lm_tile(blockIdx.x, TM, TN, tm, tn)) return;
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave & 1, wn = wave >> 1;
-  const int m0 = tm * 256, n0 = tn * 256;
+  const int m0 = tm * kLmBM, n0 = tn * kLmBN;
   G::OpA a;
   G::OpB b;
   a.init(p.w, p.ld_w, p.vocab, m0, tid);
   b.init(p.h + (int64_t)s0 * p.ld_h, p.ld_h, n_rows, n0, tid);
-  f32x16 acc[4][2];
-  G::run(acc, smem, a, b, p.d_model / 64, wm, wn, tid, lane);
+  f32x16 acc[4][kLmNB];
+  G::run(acc, smem, a, b, p.d_model / kLmBK, wm, wn, tid, lane);
 
   const int word0 = m0 + wm * 128;                 // first word of the wave
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
-    const int token = n0 + wn * 64 + 32 * nb + r;  // < tile_tokens: the tile count covers n_rows only
+  for (int nb = 0; nb < kLmNB; ++nb) {
+    const int token = n0 + wn * kLmWN + 32 * nb + r;  // < tile_tokens: the tile count covers n_rows only
     float* dst = p.logits + (int64_t)token * p.v_pad + word0 + 4 * h;
     float mx = -INFINITY;
 #pragma unroll
@@ -270,20 +289,20 @@ __global__ __launch_bounds__(256) void lm_loss_dlogits_kernel(LmHeadParams p, in
 // ---------------------------------------------------------------------------------------------
 // 3. dH_i = dLogits W_head (rows: tokens, columns: hidden, contraction: words).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kLmThreads, 1) void lm_dh_kernel(LmHeadParams p, int s0, int n_rows, int TM, int TN) {
+__global__ __launch_bounds__(kLmThreads, kLmPerCU) void lm_dh_kernel(LmHeadParams p, int s0, int n_rows, int TM, int TN) {
   using G = LmGemm<false, true>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   int tm, tn;
   if (!lm_tile(blockIdx.x, TM, TN, tm, tn)) return;
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave & 1, wn = wave >> 1;
-  const int m0 = tm * 256, n0 = tn * 256;
+  const int m0 = tm * kLmBM, n0 = tn * kLmBN;
   G::OpA a;
   G::OpB b;
   a.init(p.dlogits, p.v_pad, p.tile_tokens, m0, tid);
   b.init(p.w, p.ld_w, p.vocab, n0, tid);
-  f32x16 acc[4][2];
-  G::run(acc, smem, a, b, (p.vocab + 63) / 64, wm, wn, tid, lane);   // dLogits is zero beyond the vocabulary
+  f32x16 acc[4][kLmNB];
+  G::run(acc, smem, a, b, (p.vocab + kLmBK - 1) / kLmBK, wm, wn, tid, lane);   // dLogits is zero beyond the vocabulary
 #pragma unroll
   for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
@@ -291,8 +310,8 @@ __global__ __launch_bounds__(kLmThreads, 1) void lm_dh_kernel(LmHeadParams p, in
       const int row = m0 + wm * 128 + 32 * mb + 8 * (v >> 2) + 4 * h + (v & 3);
       if (row >= n_rows) continue;
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        const int64_t off = (int64_t)(s0 + row) * p.ld_dh + n0 + wn * 64 + 32 * nb + r;
+      for (int nb = 0; nb < kLmNB; ++nb) {
+        const int64_t off = (int64_t)(s0 + row) * p.ld_dh + n0 + wn * kLmWN + 32 * nb + r;
         if (p.dh_is_f32) ((float*)p.dh)[off] = acc[mb][nb][v];
         else ((__bf16*)p.dh)[off] = (__bf16)acc[mb][nb][v];
       }
@@ -300,34 +319,63 @@ __global__ __launch_bounds__(kLmThreads, 1) void lm_dh_kernel(LmHeadParams p, in
 }
 
 // ---------------------------------------------------------------------------------------------
-// 4. dW (+)= dLogits^T H_i (rows: words, columns: hidden, contraction: tokens of the tile).
+// 4. dW (+)= dLogits^T H_i, computed as its transpose dW^T = H_i^T dLogits (rows: hidden,
+//    columns: words, contraction: tokens of the tile).  Both factors are stored with the token as
+//    the row, and an operand read column-wise costs twice the LDS instructions of a row-wise one;
+//    the four-fragment A operand is therefore taken from a transposed copy of H_i (a few MB,
+//    written by lm_transpose_h_kernel once per sequence tile), and only the two-fragment B operand
+//    (dLogits) uses the transposing read.  A lane then owns a word: it adds four consecutive
+//    hidden columns of that word's row of dW at a time.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kLmThreads, 1) void lm_dw_kernel(LmHeadParams p, int s0, int n_rows, int TM, int TN, int accumulate) {
-  using G = LmGemm<true, true>;
+__global__ __launch_bounds__(256) void lm_transpose_h_kernel(LmHeadParams p, int s0, int n_rows) {
+  __shared__ __bf16 tile[64][66];
+  const int t0 = blockIdx.x * 64, d0 = blockIdx.y * 64, tid = threadIdx.x;   // 64 tokens x 64 hidden columns
+  for (int i = tid; i < 64 * 8; i += 256) {
+    const int tok = i >> 3, c8 = (i & 7) * 8;
+    bf16x8 x = {(__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f};
+    if (t0 + tok < n_rows) x = *reinterpret_cast<const bf16x8*>(p.h + (int64_t)(s0 + t0 + tok) * p.ld_h + d0 + c8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) tile[tok][c8 + e] = x[e];
+  }
+  __syncthreads();
+  for (int i = tid; i < 64 * 8; i += 256) {
+    const int dc = i >> 3, t8 = (i & 7) * 8;
+    bf16x8 x;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = tile[t8 + e][dc];
+    *reinterpret_cast<bf16x8*>(p.ht + (int64_t)(d0 + dc) * p.tile_tokens + t0 + t8) = x;
+  }
+}
+
+__global__ __launch_bounds__(kLmThreads, kLmPerCU) void lm_dw_kernel(LmHeadParams p, int s0, int n_rows, int TM, int TN, int accumulate) {
+  using G = LmGemm<false, true>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   int tm, tn;
   if (!lm_tile(blockIdx.x, TM, TN, tm, tn)) return;
   const int tid = threadIdx.x, lane = tid & 63, r = lane & 31, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wm = wave & 1, wn = wave >> 1;
-  const int m0 = tm * 256, n0 = tn * 256;
+  const int m0 = tm * kLmBM, n0 = tn * kLmBN;      // first hidden column, first word
   G::OpA a;
   G::OpB b;
-  a.init(p.dlogits, p.v_pad, p.tile_tokens, m0, tid);
-  b.init(p.h + (int64_t)s0 * p.ld_h, p.ld_h, n_rows, n0, tid);
-  f32x16 acc[4][2];
-  G::run(acc, smem, a, b, (n_rows + 63) / 64, wm, wn, tid, lane);    // dLogits rows beyond n_rows are zero
+  a.init(p.ht, p.tile_tokens, p.d_model, m0, tid);
+  b.init(p.dlogits, p.v_pad, p.tile_tokens, n0, tid);
+  f32x16 acc[4][kLmNB];
+  G::run(acc, smem, a, b, (n_rows + kLmBK - 1) / kLmBK, wm, wn, tid, lane);    // both factors are zero beyond n_rows
 #pragma unroll
-  for (int mb = 0; mb < 4; ++mb)
+  for (int nb = 0; nb < kLmNB; ++nb) {
+    const int word = n0 + wn * kLmWN + 32 * nb + r;
+    if (word >= p.vocab) continue;
+    float* dst = p.dw + (int64_t)word * p.ld_dw + m0 + wm * 128 + 4 * h;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int row = m0 + wm * 128 + 32 * mb + 8 * (v >> 2) + 4 * h + (v & 3);
-      if (row >= p.vocab) continue;
+    for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        float* dst = p.dw + (int64_t)row * p.ld_dw + n0 + wn * 64 + 32 * nb + r;
-        *dst = accumulate ? *dst + acc[mb][nb][v] : acc[mb][nb][v];
+      for (int g = 0; g < 4; ++g) {
+        f32x4 x = {acc[mb][nb][4 * g], acc[mb][nb][4 * g + 1], acc[mb][nb][4 * g + 2], acc[mb][nb][4 * g + 3]};
+        f32x4* q4 = reinterpret_cast<f32x4*>(dst + 32 * mb + 8 * g);
+        if (accumulate) x += *q4;
+        *q4 = x;
       }
-    }
+  }
 }
 
 __global__ __launch_bounds__(256) void lm_zero_dw_kernel(LmHeadParams p) {
@@ -339,31 +387,33 @@ __global__ __launch_bounds__(256) void lm_zero_dw_kernel(LmHeadParams p) {
 
 }  // namespace
 
-int64_t lm_head_workspace_bytes(int64_t tile_tokens, int64_t vocab) {
+int64_t lm_head_workspace_bytes(int64_t tile_tokens, int64_t vocab, int64_t d_model) {
   const int64_t v_pad = (vocab + 255) / 256 * 256;
-  return tile_tokens * v_pad * 4 + tile_tokens * v_pad * 2 + (v_pad / 128) * tile_tokens * 8;
+  return tile_tokens * v_pad * 4 + tile_tokens * v_pad * 2 + (v_pad / 128) * tile_tokens * 8 + d_model * tile_tokens * 2;
 }
 
 hipError_t launch_lm_head_loss(const LmHeadParams& p, hipStream_t stream) {
   const int want_grad = (p.dh || p.dw) ? 1 : 0;
-  const int TD = p.d_model / 256, TV = p.v_pad / 256;
-  constexpr int kLdsLogits = LmGemm<false, false>::LDS, kLdsDh = LmGemm<false, true>::LDS, kLdsDw = LmGemm<true, true>::LDS;
+  const int TD = p.d_model / kLmBN, TV = p.v_pad / kLmBM;   // column tiles of dH / dW, row tiles over the vocabulary
+  constexpr int kLdsLogits = LmGemm<false, false>::LDS, kLdsDh = LmGemm<false, true>::LDS, kLdsDw = LmGemm<false, true>::LDS;
   if (p.n_tokens == 0 && p.dw && !p.acc_dw) {
     hipLaunchKernelGGL(lm_zero_dw_kernel, dim3(2048), dim3(256), 0, stream, p);
     return hipGetLastError();
   }
   for (int s0 = 0; s0 < p.n_tokens; s0 += p.tile_tokens) {
     const int n_rows = p.n_tokens - s0 < p.tile_tokens ? p.n_tokens - s0 : p.tile_tokens;
-    const int TT = (n_rows + 255) / 256, k_rows = (n_rows + 63) / 64 * 64;
-    hipLaunchKernelGGL(lm_logits_kernel, dim3(lm_grid(TV, TT)), dim3(kLmThreads), kLdsLogits, stream, p, s0,
-                       n_rows, TV, TT);
+    const int TT = (n_rows + kLmBM - 1) / kLmBM, TTn = (n_rows + kLmBN - 1) / kLmBN, k_rows = (n_rows + 63) / 64 * 64;
+    hipLaunchKernelGGL(lm_logits_kernel, dim3(lm_grid(TV, TTn)), dim3(kLmThreads), kLdsLogits, stream, p, s0,
+                       n_rows, TV, TTn);
     hipLaunchKernelGGL(lm_loss_dlogits_kernel, dim3(want_grad ? k_rows : n_rows), dim3(256), 0, stream, p, s0, n_rows, want_grad);
     if (p.dh)
       hipLaunchKernelGGL(lm_dh_kernel, dim3(lm_grid(TT, TD)), dim3(kLmThreads), kLdsDh, stream, p, s0, n_rows,
                          TT, TD);
-    if (p.dw)
-      hipLaunchKernelGGL(lm_dw_kernel, dim3(lm_grid(TV, TD)), dim3(kLmThreads), kLdsDw, stream, p, s0, n_rows,
-                         TV, TD, (p.acc_dw || s0 > 0) ? 1 : 0);
+    if (p.dw) {
+      hipLaunchKernelGGL(lm_transpose_h_kernel, dim3(k_rows / 64, p.d_model / 64), dim3(256), 0, stream, p, s0, n_rows);
+      hipLaunchKernelGGL(lm_dw_kernel, dim3(lm_grid(p.d_model / kLmBM, p.v_pad / kLmBN)), dim3(kLmThreads), kLdsDw, stream, p,
+                         s0, n_rows, p.d_model / kLmBM, p.v_pad / kLmBN, (p.acc_dw || s0 > 0) ? 1 : 0);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

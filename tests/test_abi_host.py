@@ -341,7 +341,7 @@ def test_lm_head_arguments_are_checked_on_the_host(lib):
     ok = lib.lm_head_shape(1000, 512, 3000, 256)
     need = lib.burst_lm_head_workspace_bytes(ok)
     v_pad = 3072
-    assert need == 256 * v_pad * 4 + 256 * v_pad * 2 + (v_pad // 128) * 256 * 8
+    assert need == 256 * v_pad * 4 + 256 * v_pad * 2 + (v_pad // 128) * 256 * 8 + 512 * 256 * 2
     for bad in (lib.lm_head_shape(-1, 512, 3000, 256), lib.lm_head_shape(10, 512, 0, 256),
                 lib.lm_head_shape(10, 512, 3000, 100), lib.lm_head_shape(10, 512, 3000, 0),
                 lib.lm_head_shape(10, 0, 3000, 256), lib.lm_head_shape(10, 512, 3000, 256, float("inf"))):
