@@ -147,7 +147,7 @@ def lm_head_bench(args):
     }
     if not args.no_cpu_baseline:
         from oracle import lm_head_oracle as lmo
-        n_s = 4096
+        n_s = 8192
         Hb, Wb, Y = wl.lm_head_tensors(wl.BASE_SEED + 901, n_s, d, v)
         H64, W64 = wl.bf16_bits_to_f64(Hb), wl.bf16_bits_to_f64(Wb)
         t0 = time.perf_counter()
