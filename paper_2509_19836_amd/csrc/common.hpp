@@ -358,14 +358,18 @@ struct TileStager {
   uint32_t lds_off[PASSES];
   uint32_t src_off[PASSES];   // byte offset of this thread's chunk of pass i from the tile's first row
 
-  __device__ __forceinline__ void init(int64_t ss, int tid) {
+  // valid_rows < ROWS: load_at() reads the tile's rows beyond valid_rows - 1 as copies of that row,
+  // for tiles that reach past the end of a matrix whose extra rows must only be finite.
+  __device__ __forceinline__ void init(int64_t ss, int tid, int valid_rows = ROWS) {
     lane_off = (uint32_t)(tid / CPR) * (uint32_t)ss + (uint32_t)(tid % CPR) * 8u;
 #pragma unroll
     for (int i = 0; i < PASSES; ++i) {
       lds_off[i] = (K8 ? lds_row_k8(tid / CPR + i * RPP) : lds_row(tid / CPR + i * RPP)) * PITCH + (tid % CPR) * 16;
-      src_off[i] = 2u * ((uint32_t)(tid / CPR + i * RPP) * (uint32_t)ss + (uint32_t)(tid % CPR) * 8u);
+      src_off[i] = 2u * ((uint32_t)min(tid / CPR + i * RPP, valid_rows - 1) * (uint32_t)ss + (uint32_t)(tid % CPR) * 8u);
     }
   }
+  __device__ __forceinline__ void load_pass(const char* tile, int i) { regs[i] = *reinterpret_cast<const u32x4*>(tile + src_off[i]); }
+  __device__ __forceinline__ void store_pass(char* tile, int i) const { *reinterpret_cast<u32x4*>(tile + lds_off[i]) = regs[i]; }
   // A tile that lies wholly inside the tensor, given the (wave-uniform) address of its first row:
   // uniform base plus a precomputed 32-bit lane offset, no address arithmetic per load.
   __device__ __forceinline__ void load_at(const char* tile) {

@@ -49,41 +49,43 @@ constexpr int kLmPerCU = kLmWN == 128 ? 1 : 512 / kLmThreads;
 // One GEMM operand: where its k-tiles come from and how they are staged.  X: extent of the tile
 // along the operand's own (non-contracted) index.
 //   COLS = false: storage [x][k], k contiguous; the tile is rows x0 .. x0+X-1, columns k0 .. k0+BK-1.
-//                 lim = number of valid storage rows (rows beyond are read as the last valid row).
+//                 lim = number of valid storage rows; rows beyond are read as the last valid row
+//                 (the clamp is folded into the per-thread offsets once).
 //   COLS = true : storage [k][x], x contiguous; the tile is rows k0 .. k0+BK-1, columns x0 .. x0+X-1
 //                 (always inside the row), its rows permuted in LDS so that the column-wise read
-//                 hands out k in the row-wise operand's order.  lim = number of valid k rows
-//                 (clamped the same way).
+//                 hands out k in the row-wise operand's order.  lim = number of valid k rows: the
+//                 k-tiles that reach past it take the slower load with per-row clamping.
 template <bool COLS, int X>
 struct LmOperand {
   using Stager = std::conditional_t<COLS, TileStager<X, kLmBK, kLmThreads, true>, TileStager<kLmBK, X, kLmThreads>>;
   static constexpr int BYTES = (COLS ? kLmBK : X) * Stager::PITCH;
+  static constexpr int PASSES = Stager::PASSES;
   Stager st;
   const __bf16* base;
-  const char* tile;
+  const char* tile;     // next k-tile to stage
   int64_t ld, step;
-  int lim, x0, k0;
+  int lim, k0;
 
-  __device__ __forceinline__ void init(const __bf16* ptr, int64_t ld_, int lim_, int x0_, int tid) {
+  __device__ __forceinline__ void init(const __bf16* ptr, int64_t ld_, int lim_, int x0, int tid) {
     ld = ld_;
     lim = lim_;
-    x0 = x0_;
     k0 = 0;
     base = COLS ? ptr + x0 : ptr;
     tile = reinterpret_cast<const char*>(COLS ? ptr + x0 : ptr + (int64_t)x0 * ld);
     step = COLS ? kLmBK * ld * 2 : kLmBK * 2;
-    st.init(ld, tid);
+    st.init(ld, tid, COLS ? kLmBK : min(X, lim - x0));
   }
-  __device__ __forceinline__ void issue(int tid) {   // loads of the next k-tile
-    if (COLS) {
-      if (k0 + kLmBK <= lim) st.load_at(tile);
-      else st.load(base, ld, k0, lim, tid);
-    } else {
-      if (x0 + X <= lim) st.load_at(tile);
-      else st.load(base + k0, ld, x0, lim, tid);
-    }
+  // leading k-tiles that the plain loads can stage
+  __device__ __forceinline__ int plain_tiles(int nk) const { return COLS ? min(nk, lim / kLmBK) : nk; }
+  __device__ __forceinline__ void load_pass(int i) { st.load_pass(tile, i); }   // plain k-tiles only
+  __device__ __forceinline__ void next() {
     tile += step;
     k0 += kLmBK;
+  }
+  __device__ __forceinline__ void issue(int tid) {   // any k-tile
+    if (!COLS || k0 + kLmBK <= lim) st.load_at(tile);
+    else st.load(base, ld, k0, lim, tid);
+    next();
   }
   __device__ __forceinline__ void commit(char* lds) const { st.store(lds); }
   // fragment for the 16-wide k-step ks of the tile in LDS: lane -> row / column x_off + (lane & 31)
@@ -99,10 +101,75 @@ struct LmGemm {
   using OpB = LmOperand<B_COLS, kLmBN>;
   static constexpr int STAGE = OpA::BYTES + OpB::BYTES;
   static constexpr int LDS = 2 * STAGE;
+  static constexpr int NMFMA = 4 * kLmNB;     // MFMAs per 16-wide k-step
 
-  // acc[mb][nb]: rows 32 mb + ... of the wave's 128, columns 32 nb + ... of its 64.  nk >= 1 k-tiles.
-  // The loads of k-tile t + 1 are issued before the MFMAs of tile t and written to the other LDS
-  // buffer after them; one barrier per k-tile.
+  // The MFMAs of the k-tile in LDS buffer `cur`.  STAGE_NEXT: 0 = nothing else; 1 = the next k-tile
+  // is staged into buffer `nxt` with plain loads, one load or LDS write slipped in after every few
+  // MFMAs (loads during the first half of the k-steps, LDS writes during the second), so that the
+  // waves of a work-group, which the barrier keeps in phase, do not all queue at the memory pipe
+  // and then at the LDS write port while the matrix pipe idles; 2 = the next k-tile needs the
+  // clamping loads: issued whole before the MFMAs, written whole after them.
+  template <int STAGE_NEXT>
+  static __device__ __forceinline__ void k_tile(f32x16 (&acc)[4][kLmNB], const char* cur, char* nxt, OpA& a, OpB& b, int wm,
+                                                int wn, int tid, int lane) {
+    const char* at = cur;
+    const char* bt = cur + OpA::BYTES;
+    bf16x8 af[2][4], bf[2][kLmNB];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) af[0][mb] = OpA::frag(at, wm * 128 + 32 * mb, 0, lane);
+#pragma unroll
+    for (int nb = 0; nb < kLmNB; ++nb) bf[0][nb] = OpB::frag(bt, wn * kLmWN + 32 * nb, 0, lane);
+    if (STAGE_NEXT == 2) {
+      a.issue(tid);
+      b.issue(tid);
+    }
+    constexpr int HALF = kLmKS / 2 > 0 ? kLmKS / 2 : 1;                 // k-steps that carry loads
+    constexpr int SLOTS = HALF * NMFMA;                                 // MFMAs that may be followed by a load
+    constexpr int NOPS = OpA::PASSES + OpB::PASSES;
+    constexpr int EVERY = SLOTS / NOPS > 0 ? SLOTS / NOPS : 1;
+#pragma unroll
+    for (int ks = 0; ks < kLmKS; ++ks) {
+      if (ks + 1 < kLmKS) {
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) af[(ks + 1) & 1][mb] = OpA::frag(at, wm * 128 + 32 * mb, ks + 1, lane);
+#pragma unroll
+        for (int nb = 0; nb < kLmNB; ++nb) bf[(ks + 1) & 1][nb] = OpB::frag(bt, wn * kLmWN + 32 * nb, ks + 1, lane);
+      }
+#pragma unroll
+      for (int m = 0; m < NMFMA; ++m) {
+        const int mb = m / kLmNB, nb = m % kLmNB;
+        acc[mb][nb] = mfma32(af[ks & 1][mb], bf[ks & 1][nb], acc[mb][nb]);
+        if (STAGE_NEXT == 1) {
+          const int slot = (ks % HALF) * NMFMA + m;       // position within its half
+          if (slot % EVERY == EVERY - 1 && slot / EVERY < NOPS) {
+            const int op = slot / EVERY;
+            if (ks < HALF || kLmKS == 1) {
+              if (op < OpA::PASSES) a.load_pass(op);
+              else b.load_pass(op - OpA::PASSES);
+            }
+            if (ks >= HALF || kLmKS == 1) {
+              if (op < OpA::PASSES) a.st.store_pass(nxt, op);
+              else b.st.store_pass(nxt + OpA::BYTES, op - OpA::PASSES);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (STAGE_NEXT == 1) {
+      a.next();
+      b.next();
+    }
+    if (STAGE_NEXT == 2) {
+      a.commit(nxt);
+      b.commit(nxt + OpA::BYTES);
+    }
+  }
+
+  // acc[mb][nb]: rows 32 mb + ... of the wave's 128, columns 32 nb + ... of its kLmWN.  nk >= 1 k-tiles,
+  // double-buffered in LDS, one barrier per k-tile.  The loop over the k-tiles that plain loads can
+  // stage is free of branches.
   static __device__ __forceinline__ void run(f32x16 (&acc)[4][kLmNB], char* smem, OpA& a, OpB& b, int nk, int wm, int wn,
                                              int tid, int lane) {
 #pragma unroll
@@ -111,45 +178,24 @@ struct LmGemm {
       for (int nb = 0; nb < kLmNB; ++nb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
+    const int n_plain = min(a.plain_tiles(nk), b.plain_tiles(nk));   // k-tiles 0 .. n_plain-1 are plain
     a.issue(tid);
     b.issue(tid);
     a.commit(smem);
     b.commit(smem + OpA::BYTES);
     __syncthreads();
-    int buf = 0;
-    for (int kt = 0; kt < nk; ++kt) {
-      const bool more = kt + 1 < nk;
-      if (more) {
-        a.issue(tid);
-        b.issue(tid);
-      }
-      const char* at = smem + buf * STAGE;
-      const char* bt = at + OpA::BYTES;
-      bf16x8 af[2][4], bf[2][kLmNB];
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb) af[0][mb] = OpA::frag(at, wm * 128 + 32 * mb, 0, lane);
-#pragma unroll
-      for (int nb = 0; nb < kLmNB; ++nb) bf[0][nb] = OpB::frag(bt, wn * kLmWN + 32 * nb, 0, lane);
-#pragma unroll
-      for (int ks = 0; ks < kLmKS; ++ks) {
-        if (ks + 1 < kLmKS) {
-#pragma unroll
-          for (int mb = 0; mb < 4; ++mb) af[(ks + 1) & 1][mb] = OpA::frag(at, wm * 128 + 32 * mb, ks + 1, lane);
-#pragma unroll
-          for (int nb = 0; nb < kLmNB; ++nb) bf[(ks + 1) & 1][nb] = OpB::frag(bt, wn * kLmWN + 32 * nb, ks + 1, lane);
-        }
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-          for (int nb = 0; nb < kLmNB; ++nb) acc[mb][nb] = mfma32(af[ks & 1][mb], bf[ks & 1][nb], acc[mb][nb]);
-      }
-      if (more) {
-        a.commit(smem + (buf ^ 1) * STAGE);
-        b.commit(smem + (buf ^ 1) * STAGE + OpA::BYTES);
-      }
+    int kt = 0, buf = 0;
+    for (; kt + 1 < n_plain; ++kt) {        // stages tile kt + 1 < n_plain
+      k_tile<1>(acc, smem + buf * STAGE, smem + (buf ^ 1) * STAGE, a, b, wm, wn, tid, lane);
       __syncthreads();
       buf ^= 1;
     }
+    for (; kt + 1 < nk; ++kt) {
+      k_tile<2>(acc, smem + buf * STAGE, smem + (buf ^ 1) * STAGE, a, b, wm, wn, tid, lane);
+      __syncthreads();
+      buf ^= 1;
+    }
+    k_tile<0>(acc, smem + buf * STAGE, nullptr, a, b, wm, wn, tid, lane);
   }
 };
 
