@@ -97,7 +97,7 @@ typedef struct {
 } burst_mask_t;
 
 /*
- * Forward step (Eq. 5-6; forward algorithm lines 4-9).  For every (batch, query head):
+ * Forward step (Eq. 5-6; forward algorithm).  For every (batch, query head):
  *   S = scale * Q K^T over the visible pairs, Lse_cur = rowwise log-sum-exp(S) (natural log),
  *   O_ij = exp(S - Lse_cur) V.
  * Outputs, each optional but at least one pair required:
@@ -115,7 +115,7 @@ int burst_attn_step_fwd(const burst_shape_t* shape, const burst_mask_t* mask,
                         void* hip_stream);
 
 /*
- * Online-softmax merge of a step result into the running state (forward algorithm lines 6, 8, 9):
+ * Online-softmax merge of a step result into the running state (forward algorithm):
  * (o_acc, lse_acc) <- (o_acc, lse_acc) (+) (o_part, lse_part), with exp(-inf) = 0 so that a row
  * whose two Lse are both -inf stays (0, -inf).  o_acc fp32 in/out; o_part fp32 or bf16.
  * o_out_cast, if not NULL, also receives the merged O as bf16 (for the last step).
@@ -127,7 +127,7 @@ int burst_attn_lse_merge(const burst_shape_t* shape,
                          const burst_tensor_t* o_out_cast, void* hip_stream);
 
 /*
- * D = rowsum(dO o O), once per ring (Alg. 2 line 2).  o is fp32 or bf16, d_o is bf16,
+ * D = rowsum(dO o O), once per ring (Alg. 2).  o is fp32 or bf16, d_o is bf16,
  * d_out fp32 [batch, q_heads, sq].  Only shape->batch, q_heads, head_dim and sq are read.
  */
 int burst_attn_preprocess_bwd(const burst_shape_t* shape, const burst_tensor_t* o,
@@ -135,7 +135,7 @@ int burst_attn_preprocess_bwd(const burst_shape_t* shape, const burst_tensor_t* 
                               void* hip_stream);
 
 /*
- * Backward step (Alg. 2 lines 7-13 = Alg. 1 lines 6-13, with the softmax scale restored):
+ * Backward step (the local step that Alg. 1 and Alg. 2 share, with the softmax scale restored):
  *   S = scale * Q K^T; P = exp(S - Lse); dV += P^T dO; dP = dO V^T; dS = P o (dP - D);
  *   dK += scale * dS^T Q; dQ += scale * dS K.
  * lse and d are the FINAL (all steps merged) Lse and D of the query rows.  dq [.., sq, q_heads, ..],

@@ -19,7 +19,7 @@ Readings of the paper taken here (the paper is silent or inconsistent):
   * a masked score is excluded from the softmax (treated as -inf), as the
     causal formula Eq. 10 shows, not multiplied by zero as the sentence in
     Sec. 2.2 (4) suggests; the diagonal is visible;
-  * D is the per-row scalar rowsum(dO o O) (Alg. 2 line 2), broadcast over
+  * D is the per-row scalar rowsum(dO o O) (Alg. 2), broadcast over
     keys, not the N x N product the derivation Eq. 7-8 literally prints;
   * a query row that sees no key in a step emits (O = 0, Lse = -inf) and the
     merge treats exp(-inf) as 0, so merging it is the identity.
@@ -153,7 +153,7 @@ def attention_bwd(Q, K, V, dO, scale, vis=None):
 # ---------------------------------------------------------------------------
 
 def step_fwd(Qi, Kj, Vj, scale, vis=None):
-    """One local attention step (Eq. 5-6; forward algorithm lines 4-5, 7):
+    """One local attention step (Eq. 5-6; forward algorithm):
     S_ij = Q_i K_j^T * scale, Lse = LSE(S_ij), P_ij = exp(S_ij - Lse),
     O_ij = P_ij V_j.  Returns (O_ij, Lse_current)."""
     S = _masked_scores(Qi, Kj, scale, vis)
@@ -166,7 +166,7 @@ def step_fwd(Qi, Kj, Vj, scale, vis=None):
 
 def lse_merge(O_i, lse_i, O_ij, lse_cur):
     """Fold a step's (O_ij, Lse_current) into the running (O_i, Lse_i)
-    (forward algorithm lines 6, 8, 9):
+    (forward algorithm):
       Lse' = log(exp(Lse_i) + exp(Lse_current))
       O_i  = exp(Lse_current - Lse') O_ij + exp(Lse_i - Lse') O_i
     with exp(-inf) = 0 and (-inf, -inf) merging to (0, -inf)."""
@@ -210,13 +210,13 @@ def ring_fwd(Qi, K_shards, V_shards, scale, vis_of_shard, order):
 
 
 def preprocess_bwd(dO, O):
-    """D = rowsum(dO o O), once per ring (Alg. 2 line 2)."""
+    """D = rowsum(dO o O), once per ring (Alg. 2)."""
     return (np.asarray(dO, np.float64) * np.asarray(O, np.float64)).sum(axis=1)
 
 
 def step_bwd(Q, K, V, dO, lse, D, scale, vis=None):
-    """One backward step (Alg. 2 lines 7-13, same arithmetic as Alg. 1 lines
-    6-13) for query rows Q (with their FINAL Lse and D) against key/value
+    """One backward step (Alg. 2, same arithmetic as the local step of
+    Alg. 1) for query rows Q (with their FINAL Lse and D) against key/value
     rows K, V.  Returns this step's contributions (dQ, dK, dV):
       S = Q K^T * scale;  P = exp(S - Lse);  dV = P^T dO;  dP = dO V^T;
       dS = P o (dP - D);  dK = scale dS^T Q;  dQ = scale dS K."""
@@ -259,7 +259,7 @@ def ring_bwd_burst(i, Q_shards, dO_shards, lse_shards, D_shards, Ki, Vi, scale,
 def ring_bwd_ring(i, Qi, dOi, Oi, lse_i, K_shards, V_shards, scale, vis_of_pair, order):
     """Alg. 1 as seen from device i: Q_i, dO_i, O_i, Lse_i stay and dQ_i is
     accumulated locally; (K_j, V_j, dK_j, dV_j) visit in `order`, and D_i is
-    recomputed every round (Alg. 1 line 10).  Returns (dQ_i, {j: device i's
+    recomputed every round (Alg. 1).  Returns (dQ_i, {j: device i's
     contribution to dK_j}, {j: ... dV_j})."""
     dQ = np.zeros_like(np.asarray(Qi, np.float64))
     dK_contrib, dV_contrib = {}, {}

@@ -1,4 +1,4 @@
-// Backward step kernels (Alg. 2 lines 7-13, with the softmax scale restored):
+// Backward step kernels (Alg. 2, with the softmax scale restored):
 //   S = scale Q K^T; P = exp(S - Lse); dV += P^T dO; dP = dO V^T; dS = P o (dP - D);
 //   dK += scale dS^T Q; dQ += scale dS K.
 //

@@ -1,5 +1,5 @@
-// HBM-bound helpers: the standalone online-softmax merge (forward algorithm lines 6, 8, 9),
-// D = rowsum(dO o O) (Alg. 2 line 2), and fills.  One lane moves 16 or 32 bytes per tensor; the
+// HBM-bound helpers: the standalone online-softmax merge (forward algorithm),
+// D = rowsum(dO o O) (Alg. 2), and fills.  One lane moves 16 or 32 bytes per tensor; the
 // lanes of one row sit next to each other in one wave, so every row is read and written as
 // whole contiguous head_dim vectors.
 #include "common.hpp"

@@ -1,5 +1,5 @@
 // Forward step kernel: O_ij, Lse_cur of a query chunk against one key/value chunk (Eq. 5-6),
-// optionally folded into the running (O_i, Lse_i) in the epilogue (forward algorithm lines 6-9).
+// optionally folded into the running (O_i, Lse_i) in the epilogue (forward algorithm).
 //
 // One work-group = 8 waves = 256 query rows of one (batch, head); wave w owns rows [32w, 32w+32),
 // two waves per SIMD.  The key/value chunk streams through LDS in tiles of 64 rows, double buffered,
