@@ -28,7 +28,7 @@ def check_resources(remarks, src):
 def build(verbose=False, extra_flags=(), out_path=None, tag=""):
     """Compile every source to an object (in parallel) and link the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objdir = os.path.join(HERE, "_build" + tag)
+    objdir = os.path.join(HERE, "_build", tag) if tag else os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     procs = []
     for src in SOURCES:
