@@ -107,3 +107,52 @@ def test_llama2_vocabulary_two_sequence_tiles(lib):
     """32000 words, hidden size 1024, two sequence tiles of 1024 tokens: every output element against
     the oracle (the oracle's three fp64 products take a few seconds)."""
     run_case(lib, wl.BASE_SEED + 20008, N=2048, d=1024, v=32000, B_s=1024, grad_scale=1.0 / 2048, ignored=5)
+
+
+def test_benchmark_size_sampled_tokens_and_words(lib):
+    """The shape bench.py --lm-head times (16384 tokens, d 4096, 32000 words, sequence tiles of 8192):
+    too large for the oracle's three full products, so Lse and the loss are checked for every token
+    (the oracle's logits in fp64, in chunks), dH for sampled tokens and dW for sampled words, each
+    written out from the definition with the full-size Lse."""
+    torch = _torch()
+    N, d, v, B_s = 16384, 4096, 32000, 8192
+    gs = 1.0 / N
+    Hb, Wb, Y = wl.lm_head_tensors(wl.BASE_SEED + 20100, N, d, v, ignored=7)
+    H64, W64 = hp.widen(Hb), hp.widen(Wb)
+    rng = np.random.Generator(np.random.PCG64(wl.BASE_SEED + 20101))
+    tok = np.unique(np.concatenate([[0, 6, 7, 8191, 8192, N - 1], rng.integers(0, N, 40)]))
+    words = np.unique(np.concatenate([[0, v - 1], Y[tok[:8]].clip(0, v - 1), rng.integers(0, v, 40)]))
+    ok = (Y >= 0) & (Y < v)
+    lse_ref, tgt = np.empty(N), np.zeros(N)
+    P_words = np.empty((N, words.size))            # softmax columns of the sampled words, all tokens
+    for s0 in range(0, N, 2048):
+        logits = H64[s0:s0 + 2048] @ W64.T
+        lse_ref[s0:s0 + 2048] = lm.row_logsumexp(logits)
+        rows = np.arange(s0, min(s0 + 2048, N))
+        tgt[rows] = logits[rows - s0, np.where(ok[rows], Y[rows], 0)]
+        P_words[rows] = np.exp(logits[:, words] - lse_ref[rows, None])
+    loss_ref = np.where(ok, lse_ref - tgt, 0.0)
+    E_words = (Y[:, None] == words[None, :]).astype(np.float64)
+    dW_ref = (gs * (P_words - E_words) * ok[:, None]).T @ H64            # [words, d]
+    P_tok = np.exp(H64[tok] @ W64.T - lse_ref[tok, None])
+    E_tok = np.zeros_like(P_tok)
+    E_tok[np.nonzero(ok[tok])[0], Y[tok][ok[tok]]] = 1.0
+    dH_ref = (gs * (P_tok - E_tok) * ok[tok, None]) @ W64                # [tok, d]
+
+    shp = lib.lm_head_shape(N, d, v, B_s, gs)
+    ws = torch.empty(lib.burst_lm_head_workspace_bytes(shp), dtype=torch.uint8, device="cuda")
+    f32 = dict(dtype=torch.float32, device="cuda")
+    loss, lse = torch.empty(N, **f32), torch.empty(N, **f32)
+    dh = torch.empty(N, d, dtype=torch.bfloat16, device="cuda")
+    dw = torch.zeros(v, d, **f32)
+    print("lm head benchmark size", flush=True)
+    lib.burst_lm_head_loss(shp, _dev(Hb), _dev(Wb), torch.from_numpy(Y).cuda(), loss, ws, lse=lse, d_h=dh, d_w=dw,
+                           accumulate_dw=True)
+    torch.cuda.synchronize()
+    assert np.abs(lse.cpu().numpy() - lse_ref).max() <= hp.LSE_TOL
+    assert np.abs(loss.cpu().numpy() - loss_ref).max() <= hp.LSE_TOL
+    # the tolerance is relative to the largest entry of the whole gradient; the sample's own maximum is smaller or equal
+    got_dh = dh[torch.from_numpy(tok).cuda()].float().cpu().numpy()
+    assert np.abs(got_dh - dH_ref).max() <= hp.REL_TOL * np.abs(dH_ref).max()
+    got_dw = dw[torch.from_numpy(words).cuda()].cpu().numpy()
+    assert np.abs(got_dw - dW_ref).max() <= hp.REL_TOL * np.abs(dW_ref).max()
