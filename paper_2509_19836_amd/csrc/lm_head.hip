@@ -17,9 +17,9 @@
 // 128 x 64, 128 accumulator registers), k-tiles of 64 double-buffered in LDS, operands read from LDS
 // either row-wise (the matrix is stored with the contraction index contiguous) or column-wise with
 // the transposing LDS read (the contraction index is the storage row).  Only H_i, a few MB per
-// sequence tile, is ever transposed in memory.  The main loop is bound by LDS traffic as much as by
-// the matrix pipe (0.75 KB of operand reads per MFMA plus the staging writes against 128 B/clk),
-// which is why the wave tile is as large as 128 accumulator registers allow.
+// sequence tile, is ever transposed in memory.  The wave tile is as large as 128 accumulator
+// registers allow (0.75 KB of LDS operand reads per MFMA); the loop over the k-tiles has no branches
+// and carries the staging of the next k-tile between its MFMAs.
 #include <type_traits>
 
 #include "common.hpp"
@@ -29,10 +29,10 @@ namespace burst {
 
 namespace {
 
-// Output tile of a work-group: 256 x kLmBN, k-tiles of kLmBK, one wave per 128 x 64 sub-tile
-// (128 accumulator registers).  With kLmBN = 128 a work-group is 4 waves and two of them share a
-// CU (two waves per SIMD, from different work-groups): while one waits at its barrier or for its
-// staging loads, the other one's MFMAs keep the matrix pipe busy.
+// Output tile of a work-group: 256 x kLmBN, k-tiles of kLmBK, one wave per 128 x kLmWN sub-tile.
+// The defaults (256, 64, 64: eight waves, one work-group per CU) measured fastest; 128 x 128 wave
+// tiles at one wave per SIMD and two 256 x 128 work-groups per CU with k-tiles of 32 build from the
+// same source and were slower.
 #ifndef LM_BN
 #define LM_BN 256
 #endif
