@@ -156,3 +156,8 @@ def test_benchmark_size_sampled_tokens_and_words(lib):
     assert np.abs(got_dh - dH_ref).max() <= hp.REL_TOL * np.abs(dH_ref).max()
     got_dw = dw[torch.from_numpy(words).cuda()].cpu().numpy()
     assert np.abs(got_dw - dW_ref).max() <= hp.REL_TOL * np.abs(dW_ref).max()
+
+
+def test_llama3_vocabulary(lib):
+    """128256 words (501 vocabulary tiles of 256), hidden size 512, one ragged sequence tile: every element."""
+    run_case(lib, wl.BASE_SEED + 20009, N=1500, d=512, v=128256, B_s=2048, grad_scale=1.0 / 1500, dh_dtype="bf16", ignored=4)
