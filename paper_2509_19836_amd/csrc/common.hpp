@@ -561,6 +561,32 @@ __device__ __forceinline__ void gemm_cols(const char* tile, int row0, const bf16
   }
 }
 
+// The same product with its first PRE operands fetched by the caller ahead of time (gemm_cols_fetch),
+// e.g. before a stretch of vector work, so that the first MFMA does not wait for LDS.
+template <int PITCH, int DB, int PRE>
+__device__ __forceinline__ void gemm_cols_fetch(const char* tile, int row0, int lane, bf16x8 (&first)[PRE]) {
+#pragma unroll
+  for (int i = 0; i < PRE; ++i) first[i] = lds_cols_operand<PITCH>(tile, row0 + 16 * (i / DB), (i % DB) * 32, lane);
+}
+template <int PITCH, int DB, int NC, int PRE, class Hook = NoHook>
+__device__ __forceinline__ void gemm_cols_run(const char* tile, int row0, const bf16x8 (&b)[NC], f32x16 (&acc)[DB],
+                                              int lane, const bf16x8 (&first)[PRE], Hook&& hook = Hook()) {
+  constexpr int N = NC * DB;
+  static_assert(PRE <= N, "more operands fetched ahead than the product has");
+  bf16x8 a[N];
+  MatrixPhase prio;
+#pragma unroll
+  for (int i = 0; i < PRE; ++i) a[i] = first[i];
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    if (i + PRE < N)
+      a[i + PRE] = lds_cols_operand<PITCH>(tile, row0 + 16 * ((i + PRE) / DB), ((i + PRE) % DB) * 32, lane);
+    acc[i % DB] = mfma32(a[i], b[i / DB], acc[i % DB]);
+    if (i % DB == DB - 1) hook(i / DB);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 __device__ __forceinline__ bf16x8 pack8(const f32x16& x, int c) {
   bf16x8 o;
 #pragma unroll

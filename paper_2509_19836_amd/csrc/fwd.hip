@@ -101,6 +101,10 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
     if (cls != TILE_SKIP) {
       f32x16 s[KB];
       gemm_rows<PITCH, KB, DK, kRowsAhead, true>(kt, 0, qreg, s, r, h);
+      // the first V operands of the PV product are fetched now, ahead of the softmax arithmetic
+      bf16x8 v_first[kColsAhead];
+      gemm_cols_fetch<PITCH, DB, kColsAhead>(vt, 0, lane, v_first);
+      __builtin_amdgcn_sched_barrier(0);
       if (cls == TILE_PARTIAL) {
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) mask_tile<true>(s[kb], mk, k0 + kb * 32 + 4 * h, sk, qpos);
@@ -126,8 +130,8 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
       }
       const float msub = (m_run == -INFINITY) ? 0.f : c * m_run;
       // P = exp2(c S - c m) as packed bf16 pairs; the row sum is taken in fp32 before rounding (Lse
-      // must hold to 1e-3 also for rows with a handful of keys).  The exponentials of key block kb+1 are issued between the MFMAs of
-      // key block kb's PV product, so the vector ALU works while the matrix pipe is busy.
+      // must hold to 1e-3 also for rows with a handful of keys).  The exponentials of key block kb+1
+      // are issued between the MFMAs of key block kb's part of the PV product.
       typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
       uint32_t ppw[KB][8];
       auto exp_pairs = [&](int kb, int w0, int nw) {
@@ -141,17 +145,22 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
         }
       };
       exp_pairs(0, 0, 8);
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb) {
+      static_assert(KB == 2, "the PV product below is written for two 32-key blocks per tile");
+      // one operand stream over both key blocks: pp[2 kb], pp[2 kb + 1] are the two 16-key halves of block kb
+      bf16x8 pp[2 * KB];
+      auto pack_block = [&](int kb) {
         const u32x4 w_lo = {ppw[kb][0], ppw[kb][1], ppw[kb][2], ppw[kb][3]};
         const u32x4 w_hi = {ppw[kb][4], ppw[kb][5], ppw[kb][6], ppw[kb][7]};
-        const bf16x8 pp[2] = {__builtin_bit_cast(bf16x8, w_lo), __builtin_bit_cast(bf16x8, w_hi)};
-        if (kb + 1 < KB) {
-          gemm_cols<PITCH, DB, 2, kColsAhead>(vt, kb * 32, pp, o, lane, [&](int c2) { exp_pairs(kb + 1, 4 * c2, 4); });
-        } else {
-          gemm_cols<PITCH, DB, 2, kColsAhead>(vt, kb * 32, pp, o, lane);
-        }
-      }
+        pp[2 * kb] = __builtin_bit_cast(bf16x8, w_lo);
+        pp[2 * kb + 1] = __builtin_bit_cast(bf16x8, w_hi);
+      };
+      pack_block(0);
+      pp[2] = pp[0];   // placeholders until the hooks have produced block 1
+      pp[3] = pp[1];
+      gemm_cols_run<PITCH, DB, 2 * KB, kColsAhead>(vt, 0, pp, o, lane, v_first, [&](int c2) {
+        if (c2 < 2) exp_pairs(1, 4 * c2, 4);
+        if (c2 == 1) pack_block(1);
+      });
     }
     if (more) walk.commit(smem + (buf ^ 1) * 2 * TILE, smem + (buf ^ 1) * 2 * TILE + TILE);
     __syncthreads();
