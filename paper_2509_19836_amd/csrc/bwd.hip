@@ -121,14 +121,14 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_bwd_dq_kernel(B
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb) {
         f32x16 sd[2];   // S^T and dP^T of this key block: two independent accumulator chains
-        zero16(sd[0]);
-        zero16(sd[1]);
-        gemm_rows_pair<PITCH, DK, kRowsAhead>(kt, vt, kb * 32, qreg, doreg, sd[0], sd[1], r, h);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sd[1][v] = -dval;   // dP - D comes out of the GEMM: the lane owns the row, D is its constant
+        gemm_rows_pair<PITCH, DK, kRowsAhead, true>(kt, vt, kb * 32, qreg, doreg, sd[0], sd[1], r, h);   // sd[0] starts from a literal zero
         if (cls == TILE_PARTIAL) mask_tile<true>(sd[0], mk, k0 + kb * 32 + 4 * h, sk, qpos);
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           float pr = __builtin_amdgcn_exp2f(c * sd[0][v] - lse2);
-          sd[0][v] = pr * (sd[1][v] - dval);
+          sd[0][v] = pr * sd[1][v];
         }
         bf16x8 ds[2] = {pack8(sd[0], 0), pack8(sd[0], 1)};
         gemm_cols<PITCH, DB, 2, kColsAhead>(kt, kb * 32, ds, dq, lane);
@@ -296,7 +296,7 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
     stage_q.store(smem + L::Q_OFF + q_slot * TILE);
     stage_do.store(smem + L::DO_OFF + par * TILE);
     if (tid < BQ) lse_slots[par * BQ + tid] = lse_to_log2(stage_row);
-    else if (tid < 2 * BQ) d_slots[q_slot * BQ + tid - BQ] = stage_row;
+    else if (tid < 2 * BQ) d_slots[q_slot * BQ + tid - BQ] = -stage_row;   // -D: the dS-wave's dP accumulators start from it
   };
 
   wait_global_loads();
@@ -335,9 +335,7 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
         bf16x8* pw = pbuf + par * L::P_SLOT;
         bf16x8 pk[2 * QBK];
         f32x16 s[QBK];
-#pragma unroll
-        for (int qb = 0; qb < QBK; ++qb) zero16(s[qb]);
-        gemm_rows<PITCH, QBK, DK, kRowsAhead>(qt_, 0, xreg, s, r, h);
+        gemm_rows<PITCH, QBK, DK, kRowsAhead, true>(qt_, 0, xreg, s, r, h);   // first MFMA of each block adds to a literal zero
 #pragma unroll
         for (int qb = 0; qb < QBK; ++qb) {
           if (cls == TILE_PARTIAL) mask_tile<false>(s[qb], mk, q0 + qb * 32 + 4 * h, sq, kpos);
@@ -357,7 +355,6 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
     } else {
       if (cls_prev != TILE_SKIP) {
         const char* qt_ = smem + L::Q_OFF + qs_prev * TILE;
-        const float* dv_ = d_slots + qs_prev * BQ;
         const bf16x8* pr_ = pbuf + (par ^ 1) * L::P_SLOT;
         bf16x8 dsp[2 * QBK];
 #pragma unroll
@@ -365,14 +362,9 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
           const bf16x8 p0 = pr_[((pair * QBK + qb) * 2 + 0) * 64 + lane];
           const bf16x8 p1 = pr_[((pair * QBK + qb) * 2 + 1) * 64 + lane];
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const f32x4 d4 = *reinterpret_cast<const f32x4*>(dv_ + qb * 32 + 8 * g + 4 * h);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const int v = 4 * g + j;
-              const float pr = (float)(v < 8 ? p0[v & 7] : p1[v & 7]);
-              dp[qb][v] = pr * (dp[qb][v] - d4[j]);
-            }
+          for (int v = 0; v < 16; ++v) {
+            const float pr = (float)(v < 8 ? p0[v & 7] : p1[v & 7]);
+            dp[qb][v] = pr * dp[qb][v];   // dp already holds dP - D
           }
           dsp[2 * qb] = pack8(dp[qb], 0);
           dsp[2 * qb + 1] = pack8(dp[qb], 1);
@@ -380,8 +372,16 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
         gemm_cols<PITCH, DB, 2 * QBK, kColsAhead>(qt_, 0, dsp, acc, lane);
       }
       if (cls != TILE_SKIP) {
+        // dP - D: the accumulators start from -D of their query rows (registers run over rows here)
+        const float* nd_ = d_slots + qs_cur * BQ;
 #pragma unroll
-        for (int qb = 0; qb < QBK; ++qb) zero16(dp[qb]);
+        for (int qb = 0; qb < QBK; ++qb)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const f32x4 d4 = *reinterpret_cast<const f32x4*>(nd_ + qb * 32 + 8 * g + 4 * h);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dp[qb][4 * g + j] = d4[j];
+          }
         gemm_rows<PITCH, QBK, DK, kRowsAhead>(dot_, 0, xreg, dp, r, h);
       }
     }

@@ -517,7 +517,7 @@ __device__ __forceinline__ void gemm_rows(const char* tile, int row0, const bf16
 
 // Two row-wise GEMMs sharing the row block, interleaved so consecutive MFMAs alternate between the
 // two accumulators:  acc0 += rows(tile0) * b0,  acc1 += rows(tile1) * b1.
-template <int PITCH, int DK, int PRE>
+template <int PITCH, int DK, int PRE, bool ZERO0 = false>   // ZERO0: acc0 starts from zero (not read)
 __device__ __forceinline__ void gemm_rows_pair(const char* tile0, const char* tile1, int row0, const bf16x8 (&b0)[DK],
                                                const bf16x8 (&b1)[DK], f32x16& acc0, f32x16& acc1, int r, int h) {
   bf16x8 a0[DK], a1[DK];
@@ -533,7 +533,7 @@ __device__ __forceinline__ void gemm_rows_pair(const char* tile0, const char* ti
       a0[ks + PRE] = lds_rows_operand<PITCH>(tile0, row0, (ks + PRE) * 16, r, h);
       a1[ks + PRE] = lds_rows_operand<PITCH>(tile1, row0, (ks + PRE) * 16, r, h);
     }
-    acc0 = mfma32(a0[ks], b0[ks], acc0);
+    acc0 = mfma32(a0[ks], b0[ks], (ZERO0 && ks == 0) ? f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f} : acc0);
     acc1 = mfma32(a1[ks], b1[ks], acc1);
     __builtin_amdgcn_sched_barrier(0);
   }
