@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flo
 # command (profiles/bench_config2_pmc_hbm_traffic.md: counter means over the ring, scaled by what the
 # same counters read for the 1 GiB copy issued below).  Counters cannot be read from inside the
 # process, so the figure is the profiled one and exists for the profiled workload only.
-PROFILED_TRAFFIC_BYTES = {2: 1.908e9}
+PROFILED_TRAFFIC_BYTES = {2: 1.922e9}
 # --lm-head, default shape: bytes per call over all its launches (profiles/bench_lm_head_kernel_trace_and_counters.md)
 PROFILED_LM_HEAD_TRAFFIC_BYTES = 2.73e10
 
