@@ -38,7 +38,8 @@ typedef enum {
   BURST_OK = 0,
   BURST_ERR_INVALID_ARG = -1, /* null pointer, bad size/stride/alignment, inconsistent mask */
   BURST_ERR_UNSUPPORTED = -2, /* valid request this build has no kernel for (dtype, head_dim) */
-  BURST_ERR_HIP = -3          /* a HIP call failed; see burst_attn_last_hip_error() */
+  BURST_ERR_HIP = -3,         /* a HIP call failed; see burst_attn_last_hip_error() */
+  BURST_ERR_SCRATCH = -4      /* the shape needs more scratch than the library's built-in buffer holds */
 } burst_status_t;
 
 typedef enum { BURST_BF16 = 0, BURST_F32 = 1 } burst_dtype_t;

@@ -63,6 +63,28 @@ int burst_lm_head_loss(const burst_lm_head_shape_t* shape, const void* h_last, i
                        void* d_h, int32_t d_h_dtype, int64_t ld_dh, float* d_w, int64_t ld_dw,
                        int32_t accumulate_dw, void* workspace, int64_t workspace_bytes, void* hip_stream);
 
+/*
+ * The same computation for callers that cannot allocate device memory or hand over a workspace of
+ * their own: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Arguments, results and errors are those of burst_lm_head_loss without the workspace
+ * pair: the scratch memory is an array built into the library's code object, 64 MiB per GPU
+ * (burst_lm_head_static_scratch_bytes()), present from the moment the library is loaded until the
+ * process ends.  The call allocates nothing and frees nothing, on the host or on the device.
+ *   - A shape whose burst_lm_head_workspace_bytes() exceeds that size is refused with
+ *     BURST_ERR_SCRATCH and nothing is enqueued (64 MiB holds e.g. tile_tokens = 256 with a
+ *     32000-word vocabulary and d = 4096); choose a smaller tile_tokens or use burst_lm_head_loss.
+ *   - The array used is that of the GPU that is current on the calling thread when the call is
+ *     made; the stream must belong to that GPU.
+ *   - Every call on a GPU shares that GPU's array, which keeps whatever the last call left in it
+ *     (no call depends on its previous contents).  Calls that may overlap on one GPU -- different
+ *     streams, or this entry point from two threads -- race on it: order them on one stream.
+ */
+int64_t burst_lm_head_static_scratch_bytes(void);
+int burst_lm_head_loss_noalloc(const burst_lm_head_shape_t* shape, const void* h_last, int64_t ld_h,
+                               const void* w_head, int64_t ld_w, const int64_t* y, float* loss, float* lse,
+                               void* d_h, int32_t d_h_dtype, int64_t ld_dh, float* d_w, int64_t ld_dw,
+                               int32_t accumulate_dw, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,7 @@ if not os.path.exists(LIB_PATH):
         "__graft_entry__.build()); libburstattn has no CPU or PyTorch fallback")
 _lib = C.CDLL(LIB_PATH)
 
-BURST_OK, BURST_ERR_INVALID_ARG, BURST_ERR_UNSUPPORTED, BURST_ERR_HIP = 0, -1, -2, -3
+BURST_OK, BURST_ERR_INVALID_ARG, BURST_ERR_UNSUPPORTED, BURST_ERR_HIP, BURST_ERR_SCRATCH = 0, -1, -2, -3, -4
 BURST_BF16, BURST_F32 = 0, 1
 BURST_MASK_FULL, BURST_MASK_CAUSAL = 0, 1
 BURST_ACC_DQ, BURST_ACC_DK, BURST_ACC_DV = 1, 2, 4
@@ -85,6 +85,12 @@ _lib.burst_lm_head_loss.restype = C.c_int
 _lib.burst_lm_head_loss.argtypes = [_P(burst_lm_head_shape_t), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_int64,
                                     C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
+_lib.burst_lm_head_static_scratch_bytes.restype = C.c_int64
+_lib.burst_lm_head_static_scratch_bytes.argtypes = []
+_lib.burst_lm_head_loss_noalloc.restype = C.c_int
+_lib.burst_lm_head_loss_noalloc.argtypes = [_P(burst_lm_head_shape_t), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_int64,
+                                            C.c_int32, C.c_void_p]
 _lib.burst_attn_status_string.restype = C.c_char_p
 _lib.burst_attn_status_string.argtypes = [C.c_int]
 _lib.burst_attn_last_hip_error.restype = C.c_int
@@ -93,7 +99,8 @@ _lib.burst_attn_version.restype = C.c_char_p
 EXPORTS = ["burst_attn_step_fwd", "burst_attn_lse_merge", "burst_attn_preprocess_bwd", "burst_attn_step_bwd",
            "burst_attn_fill_zigzag_mask", "burst_attn_fill_contiguous_mask", "burst_attn_fill_striped_mask",
            "burst_attn_visible_pairs", "burst_attn_tile_class", "burst_attn_visible_tile_runs", "burst_attn_mfma_probe", "burst_attn_status_string", "burst_attn_last_hip_error",
-           "burst_attn_version", "burst_lm_head_workspace_bytes", "burst_lm_head_loss"]
+           "burst_attn_version", "burst_lm_head_workspace_bytes", "burst_lm_head_loss",
+           "burst_lm_head_static_scratch_bytes", "burst_lm_head_loss_noalloc"]
 
 
 class BurstError(RuntimeError):
@@ -247,6 +254,27 @@ def burst_lm_head_loss(shp, h_last, w_head, y, loss, workspace, lse=None, d_h=No
                                    ptr(loss), ptr(lse), ptr(d_h), dh_dtype, 0 if d_h is None else d_h.stride(0),
                                    ptr(d_w), 0 if d_w is None else d_w.stride(0), int(accumulate_dw),
                                    ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def burst_lm_head_static_scratch_bytes():
+    return _lib.burst_lm_head_static_scratch_bytes()
+
+
+def burst_lm_head_loss_noalloc(shp, h_last, w_head, y, loss, lse=None, d_h=None, d_w=None, accumulate_dw=False,
+                               stream=None):
+    """burst_lm_head_loss on the library's built-in scratch array (no workspace argument, no allocation)."""
+    for t in (h_last, w_head, d_h, d_w):
+        assert t is None or (t.dim() == 2 and t.stride(1) == 1), "expected 2-D tensors with a contiguous last dim"
+    assert h_last.dtype == torch.bfloat16 and w_head.dtype == torch.bfloat16 and y.dtype == torch.int64
+    assert y.is_contiguous() and loss.is_contiguous() and loss.dtype == torch.float32
+    assert lse is None or (lse.is_contiguous() and lse.dtype == torch.float32)
+    assert d_w is None or d_w.dtype == torch.float32
+    ptr = lambda t: None if t is None else C.c_void_p(t.data_ptr())
+    dh_dtype = BURST_F32 if d_h is None else {torch.bfloat16: BURST_BF16, torch.float32: BURST_F32}[d_h.dtype]
+    _check(_lib.burst_lm_head_loss_noalloc(C.byref(shp), ptr(h_last), h_last.stride(0), ptr(w_head), w_head.stride(0),
+                                           ptr(y), ptr(loss), ptr(lse), ptr(d_h), dh_dtype,
+                                           0 if d_h is None else d_h.stride(0), ptr(d_w),
+                                           0 if d_w is None else d_w.stride(0), int(accumulate_dw), _stream(stream)))
 
 
 def burst_attn_mfma_probe(random_operands, iterations, stream=None):

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "../../include/burst_attn.h"
 #include "../../include/burst_lm_head.h"
@@ -109,6 +110,31 @@ int check_mask(const burst_mask_t* m, int64_t sq, int64_t sk, MaskDev* out) {
     out->blk_k = (int32_t)(m->k_block_rows > INT32_MAX ? INT32_MAX - 127 : m->k_block_rows);
     out->blk_pitch = (int32_t)m->block_pitch;
   }
+  return BURST_OK;
+}
+
+// Scratch memory of burst_lm_head_loss_noalloc: one array per GPU, part of the loaded code object,
+// so the entry point never allocates.  The array's name is only a host-side handle: kernels get the
+// device address that hipGetSymbolAddress reports for the current device, looked up once per device.
+constexpr int64_t kStaticScratchBytes = (int64_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (dev < 0 || dev >= kMaxDevices) return BURST_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));   // the address on the current device
+    if (e != hipSuccess || !ptr) return hip_fail(e == hipSuccess ? hipErrorInvalidSymbol : e);
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
   return BURST_OK;
 }
 
@@ -403,11 +429,11 @@ int64_t burst_lm_head_workspace_bytes(const burst_lm_head_shape_t* shape) {
   return lm_head_workspace_bytes(shape->tile_tokens, shape->vocab, shape->d_model);
 }
 
-int burst_lm_head_loss(const burst_lm_head_shape_t* shape, const void* h_last, int64_t ld_h, const void* w_head,
-                       int64_t ld_w, const int64_t* y, float* loss, float* lse, void* d_h, int32_t d_h_dtype,
-                       int64_t ld_dh, float* d_w, int64_t ld_dw, int32_t accumulate_dw, void* workspace,
-                       int64_t workspace_bytes, void* hip_stream) {
-  BURST_TRY(check_lm_shape(shape));
+// Checks and launch shared by the two entry points; `workspace` is already known to be large enough.
+static int lm_head_loss_on(const burst_lm_head_shape_t* shape, const void* h_last, int64_t ld_h, const void* w_head,
+                           int64_t ld_w, const int64_t* y, float* loss, float* lse, void* d_h, int32_t d_h_dtype,
+                           int64_t ld_dh, float* d_w, int64_t ld_dw, int32_t accumulate_dw, void* workspace,
+                           void* hip_stream) {
   const int64_t d = shape->d_model, max_ld = (int64_t)1 << 22;
   auto aligned = [](const void* ptr, uintptr_t a) { return ptr && (reinterpret_cast<uintptr_t>(ptr) % a) == 0; };
   if (!aligned(w_head, 16)) return BURST_ERR_INVALID_ARG;
@@ -424,8 +450,6 @@ int burst_lm_head_loss(const burst_lm_head_shape_t* shape, const void* h_last, i
     if (!aligned(d_w, 16) || ld_dw < d || ld_dw % 4 != 0) return BURST_ERR_INVALID_ARG;
     if (ld_dw > max_ld) return BURST_ERR_UNSUPPORTED;
   }
-  if (!aligned(workspace, 256) || workspace_bytes < lm_head_workspace_bytes(shape->tile_tokens, shape->vocab, shape->d_model))
-    return BURST_ERR_INVALID_ARG;
   LmHeadParams p;
   std::memset(&p, 0, sizeof(p));
   p.n_tokens = (int32_t)shape->n_tokens;
@@ -457,12 +481,40 @@ int burst_lm_head_loss(const burst_lm_head_shape_t* shape, const void* h_last, i
   return e == hipSuccess ? BURST_OK : hip_fail(e);
 }
 
+int burst_lm_head_loss(const burst_lm_head_shape_t* shape, const void* h_last, int64_t ld_h, const void* w_head,
+                       int64_t ld_w, const int64_t* y, float* loss, float* lse, void* d_h, int32_t d_h_dtype,
+                       int64_t ld_dh, float* d_w, int64_t ld_dw, int32_t accumulate_dw, void* workspace,
+                       int64_t workspace_bytes, void* hip_stream) {
+  BURST_TRY(check_lm_shape(shape));
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % 256) != 0 ||
+      workspace_bytes < lm_head_workspace_bytes(shape->tile_tokens, shape->vocab, shape->d_model))
+    return BURST_ERR_INVALID_ARG;
+  return lm_head_loss_on(shape, h_last, ld_h, w_head, ld_w, y, loss, lse, d_h, d_h_dtype, ld_dh, d_w, ld_dw, accumulate_dw,
+                         workspace, hip_stream);
+}
+
+int64_t burst_lm_head_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int burst_lm_head_loss_noalloc(const burst_lm_head_shape_t* shape, const void* h_last, int64_t ld_h,
+                               const void* w_head, int64_t ld_w, const int64_t* y, float* loss, float* lse, void* d_h,
+                               int32_t d_h_dtype, int64_t ld_dh, float* d_w, int64_t ld_dw, int32_t accumulate_dw,
+                               void* hip_stream) {
+  BURST_TRY(check_lm_shape(shape));
+  if (lm_head_workspace_bytes(shape->tile_tokens, shape->vocab, shape->d_model) > kStaticScratchBytes)
+    return BURST_ERR_SCRATCH;
+  void* ws = nullptr;
+  BURST_TRY(static_scratch_of_current_device(&ws));
+  return lm_head_loss_on(shape, h_last, ld_h, w_head, ld_w, y, loss, lse, d_h, d_h_dtype, ld_dh, d_w, ld_dw, accumulate_dw,
+                         ws, hip_stream);
+}
+
 const char* burst_attn_status_string(int status) {
   switch (status) {
     case BURST_OK: return "ok";
     case BURST_ERR_INVALID_ARG: return "invalid argument";
     case BURST_ERR_UNSUPPORTED: return "unsupported dtype, head_dim or position range";
     case BURST_ERR_HIP: return "HIP runtime error";
+    case BURST_ERR_SCRATCH: return "the shape needs more scratch memory than the library's built-in buffer holds";
     default: return "unknown status";
   }
 }

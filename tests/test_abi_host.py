@@ -359,3 +359,22 @@ def test_lm_head_arguments_are_checked_on_the_host(lib):
     assert call(ld_h=504) == INV and call(ld_w=511) == INV                 # leading dimension below d / not a multiple of 8
     assert call(dh_dtype=7) == INV and call(ld_dh=256) == INV and call(ld_dw=510) == INV
     assert call(ws=None) == INV and call(ws=0x70010) == INV and call(ws_bytes=need - 1) == INV
+
+
+def test_lm_head_noalloc_entry_point_checks_shape_and_scratch_limit_on_the_host(lib):
+    """burst_lm_head_loss_noalloc refuses, before touching any GPU, an invalid shape and a shape whose
+    workspace exceeds the library's built-in scratch array; the pointers are never dereferenced."""
+    raw = lib.raw()
+    limit = lib.burst_lm_head_static_scratch_bytes()
+    assert limit == 64 << 20
+
+    def call(shape):
+        return raw.burst_lm_head_loss_noalloc(C.byref(shape) if shape is not None else None, 0x10000, 512, 0x20000, 512,
+                                              0x30000, 0x40000, None, 0x50000, 1, 512, 0x60000, 512, 0, None)
+    assert call(None) == lib.BURST_ERR_INVALID_ARG
+    assert call(lib.lm_head_shape(1000, 500, 3000, 256)) == lib.BURST_ERR_UNSUPPORTED
+    fits = lib.lm_head_shape(1000, 4096, 32000, 256)
+    too_big = lib.lm_head_shape(1000, 4096, 32000, 512)
+    assert lib.burst_lm_head_workspace_bytes(fits) <= limit < lib.burst_lm_head_workspace_bytes(too_big)
+    assert call(too_big) == lib.BURST_ERR_SCRATCH
+    assert "scratch" in lib.burst_attn_status_string(lib.BURST_ERR_SCRATCH)
