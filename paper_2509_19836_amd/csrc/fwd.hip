@@ -208,13 +208,17 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
     const float tot = e_old + e_cur;
     const float lse_new = mm + __logf(tot);
     const float w_old = e_old / tot, w_cur_n = e_cur / tot * inv;
+    const bool has_old = lse_old != -INFINITY;
     float* dst = (float*)p.o_acc.ptr + b * p.o_acc.sb + (int64_t)orow * p.o_acc.ss + hq * p.o_acc.sh;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         float* q4 = dst + db * 32 + 8 * g + 4 * h;
-        const f32x4 old = *reinterpret_cast<const f32x4*>(q4);
+        // a running state that is still (anything, -inf) has weight zero and is not read as a number:
+        // the buffer may hold whatever it was allocated with (0 * NaN would poison the row)
+        f32x4 old = *reinterpret_cast<const f32x4*>(q4);
+        if (!has_old) old = f32x4{0.f, 0.f, 0.f, 0.f};
         f32x4 x = {o[db][4 * g] * w_cur_n + old[0] * w_old, o[db][4 * g + 1] * w_cur_n + old[1] * w_old,
                    o[db][4 * g + 2] * w_cur_n + old[2] * w_old, o[db][4 * g + 3] * w_cur_n + old[3] * w_old};
         *reinterpret_cast<f32x4*>(q4) = x;

@@ -20,9 +20,25 @@ def _sample_rows(n, seg, rng, extra=24):
     return np.array(sorted(rows), dtype=np.int64)
 
 
-def _step_sampled(lib, B, n, Hq, Hkv, d, mask, scale, seed, head_scale=False, batch_index=0, heads=None):
-    """One forward and one backward step at the given size; whole sampled query rows and whole sampled
-    key rows of a few heads against the oracle."""
+def _assert_close(got, ref, partners, what):
+    """max |got - ref| <= 2e-2 max|ref|, with the sampled rows split by how many partners (visible keys
+    of a query row, visible queries of a key row) they have: rows with a handful of partners are
+    O(1) in size and would hide an error in rows that average over thousands, so each group is held
+    to its own largest reference entry.  The denominators come from the oracle alone."""
+    for name, sel in (("few", (partners > 0) & (partners < 64)), ("many", partners >= 64)):
+        if not sel.any():
+            continue
+        denom = np.abs(ref[sel]).max()
+        err = np.abs(got[sel] - ref[sel]).max()
+        assert err <= hp.REL_TOL * denom, (what, name, err, denom)
+    dead = partners == 0
+    assert (got[dead] == 0).all(), (what, "rows without a partner must be exactly zero")
+
+
+def _step_sampled(lib, B, n, Hq, Hkv, d, mask, scale, seed, head_scale=False, batch_index=0, heads=None, kv_heads=None):
+    """One forward and one backward step at the given size; whole sampled query rows (O, Lse, dQ) of a
+    few query heads and whole sampled key rows (dK, dV) of a few KV heads against the oracle; with
+    grouped heads the oracle's dK / dV are summed over the query heads of the group."""
     import torch
     gen = torch.Generator(device="cuda")
     gen.manual_seed(seed)
@@ -40,13 +56,18 @@ def _step_sampled(lib, B, n, Hq, Hkv, d, mask, scale, seed, head_scale=False, ba
     f32 = dict(device="cuda", dtype=torch.float32)
     o_part = torch.empty(B, n, Hq, d, **f32)
     lse_part = torch.empty(B, Hq, n, **f32)
+    print(f"step fwd B={B} n={n} Hq={Hq} Hkv={Hkv}", flush=True)
     lib.burst_attn_step_fwd(shp, mask, q, k, v, o_part=o_part, lse_part=lse_part)
-    # backward inputs as a longer ring would deliver them: a larger, finite Lse and some D
+    # Backward inputs as a longer ring would deliver them: a larger, finite Lse and some D.  They derive
+    # from this step's own forward result (checked against the oracle below) only to be of a realistic
+    # size; the backward step is a function of whatever (Lse, D) it is given, and the oracle is handed
+    # the same values.
     lse_in = torch.where(torch.isfinite(lse_part), lse_part + 0.5, torch.full_like(lse_part, 3.0))
     d_in = torch.randn(B, Hq, n, device="cuda", generator=gen)
     dq = torch.full((B, n, Hq, d), float("nan"), **f32)
     dk = torch.full((B, n, Hkv, d), float("nan"), **f32)
     dv = torch.full((B, n, Hkv, d), float("nan"), **f32)
+    print("step bwd", flush=True)
     lib.burst_attn_step_bwd(shp, mask, q, k, v, do, lse_in, d_in, dq=dq, dk=dk, dv=dv)
     torch.cuda.synchronize()
     assert torch.isfinite(dq).all() and torch.isfinite(dk).all() and torch.isfinite(dv).all()
@@ -56,31 +77,30 @@ def _step_sampled(lib, B, n, Hq, Hkv, d, mask, scale, seed, head_scale=False, ba
     cols = _sample_rows(n, n // 2, rng)
     to64 = lambda t: t.float().cpu().numpy().astype(np.float64)
     bi, group = batch_index, Hq // Hkv
+    vis_r = oc.visibility(qpos[rows], kpos, causal, mask.window)
+    keys_seen = vis_r.sum(axis=1)
     for head in heads or (0, Hq - 1):
         kvh = head // group
         Qh, dOh, Kh, Vh = to64(q[bi, :, head]), to64(do[bi, :, head]), to64(k[bi, :, kvh]), to64(v[bi, :, kvh])
         lse_h, d_h = to64(lse_in[bi, head]), to64(d_in[bi, head])
-        # whole query rows
-        vis_r = oc.visibility(qpos[rows], kpos, causal, mask.window)
         O_ref, lse_ref = oc.step_fwd(Qh[rows], Kh, Vh, scale, vis_r)
-        o_scale = np.abs(to64(o_part[bi, :, head])).max()
-        assert np.abs(to64(o_part[bi, :, head])[rows] - O_ref).max() <= hp.REL_TOL * o_scale
+        _assert_close(to64(o_part[bi, :, head])[rows], O_ref, keys_seen, f"O head {head}")
         assert hp.lse_err(to64(lse_part[bi, head])[rows], lse_ref) <= hp.LSE_TOL
         dQ_ref, _, _ = oc.step_bwd(Qh[rows], Kh, Vh, dOh[rows], lse_h[rows], d_h[rows], scale, vis_r)
-        dq_scale = np.abs(to64(dq[bi, :, head])).max()
-        assert np.abs(to64(dq[bi, :, head])[rows] - dQ_ref).max() <= hp.REL_TOL * dq_scale
-        # rows the mask empties entirely must be exactly (0, -inf) / 0
-        dead_r = ~vis_r.any(axis=1)
-        assert (to64(o_part[bi, :, head])[rows][dead_r] == 0).all()
-        assert (to64(dq[bi, :, head])[rows][dead_r] == 0).all()
-        if group == 1:   # whole key rows (with grouped heads dK / dV sum over the group: tested separately)
-            vis_c = oc.visibility(qpos, kpos[cols], causal, mask.window)
-            _, dK_ref, dV_ref = oc.step_bwd(Qh, Kh[cols], Vh[cols], dOh, lse_h, d_h, scale, vis_c)
-            dk_scale, dv_scale = np.abs(to64(dk[bi, :, head])).max(), np.abs(to64(dv[bi, :, head])).max()
-            assert np.abs(to64(dk[bi, :, head])[cols] - dK_ref).max() <= hp.REL_TOL * dk_scale
-            assert np.abs(to64(dv[bi, :, head])[cols] - dV_ref).max() <= hp.REL_TOL * dv_scale
-            dead_c = ~vis_c.any(axis=0)
-            assert (to64(dk[bi, :, head])[cols][dead_c] == 0).all() and (to64(dv[bi, :, head])[cols][dead_c] == 0).all()
+        _assert_close(to64(dq[bi, :, head])[rows], dQ_ref, keys_seen, f"dQ head {head}")
+    # whole key rows: dK / dV of a KV head collect every query head of its group
+    vis_c = oc.visibility(qpos, kpos[cols], causal, mask.window)
+    queries_seeing = vis_c.sum(axis=0)
+    for kvh in kv_heads if kv_heads is not None else sorted({h_ // group for h_ in (heads or (0, Hq - 1))}):
+        Kc, Vc = to64(k[bi, :, kvh])[cols], to64(v[bi, :, kvh])[cols]
+        dK_ref, dV_ref = np.zeros((cols.size, d)), np.zeros((cols.size, d))
+        for head in range(kvh * group, (kvh + 1) * group):
+            _, dk_h, dv_h = oc.step_bwd(to64(q[bi, :, head]), Kc, Vc, to64(do[bi, :, head]), to64(lse_in[bi, head]),
+                                        to64(d_in[bi, head]), scale, vis_c)
+            dK_ref += dk_h
+            dV_ref += dv_h
+        _assert_close(to64(dk[bi, :, kvh])[cols], dK_ref, queries_seeing, f"dK kv head {kvh}")
+        _assert_close(to64(dv[bi, :, kvh])[cols], dV_ref, queries_seeing, f"dV kv head {kvh}")
 
 
 @pytest.mark.parametrize("shard_j", [3, 1, 5])
@@ -113,21 +133,26 @@ def test_config4_full_mask_head_scales_sampled_rows(lib):
                   wl.BASE_SEED + 500, head_scale=True, batch_index=1, heads=(13,))
 
 
-def test_config3_gqa_launch_shape_sampled_rows(lib):
+@pytest.mark.parametrize("shard_j", [5, 3])
+def test_config3_gqa_launch_shape_sampled_rows(lib, shard_j):
     """Config 3's launch configuration (64 query heads on 8 KV heads, 32768-row chunks): sampled query
-    rows of two heads of different groups (the group sum of dK / dV is checked at a smaller size below)."""
+    rows of two heads of different groups, and sampled key rows of one KV head against the oracle summed
+    over the 8 query heads of its group (the in-register group reduction at its real shape)."""
     w = wl.WORKLOADS[3]
-    mask = lib.burst_attn_fill_zigzag_mask(3, 5, w.shards, w.seq)
+    mask = lib.burst_attn_fill_zigzag_mask(3, shard_j, w.shards, w.seq)
     _step_sampled(lib, w.batch, w.shard_tokens, w.q_heads, w.kv_heads, w.head_dim, mask, w.scale,
-                  wl.BASE_SEED + 600, heads=(9, 62))
+                  wl.BASE_SEED + 600 + shard_j, heads=(9, 62), kv_heads=(7,))
 
 
-def test_config5_million_token_launch_shape_sampled_rows(lib):
-    """Config 5's launch configuration: 131072-row chunks of a 1M-token sequence, own-shard step."""
+@pytest.mark.parametrize("shard_j", [3, 1, 6])
+def test_config5_million_token_launch_shape_sampled_rows(lib, shard_j):
+    """Config 5's launch configuration, the one bench.py times: 131072-row chunks of a 1M-token sequence,
+    device 3 against its own shard, an earlier shard (j < i) and a later one (j > i), where the two-run
+    tile walks and the 32-bit offsets inside a chunk are stretched furthest."""
     w = wl.WORKLOADS[5]
-    mask = lib.burst_attn_fill_zigzag_mask(3, 3, w.shards, w.seq)
+    mask = lib.burst_attn_fill_zigzag_mask(3, shard_j, w.shards, w.seq)
     _step_sampled(lib, w.batch, w.shard_tokens, w.q_heads, w.kv_heads, w.head_dim, mask, w.scale,
-                  wl.BASE_SEED + 700, heads=(21,))
+                  wl.BASE_SEED + 700 + shard_j, heads=(21,))
 
 
 def test_gqa_full_size_heads_group_reduction(lib):
@@ -163,5 +188,6 @@ def test_gqa_full_size_heads_group_reduction(lib):
                                     to64(lse_in[0, hq]), to64(d_in[0, hq]), scale, vis_c)
         dK_ref += dk_h
         dV_ref += dv_h
-    assert np.abs(to64(dk[0, :, g])[cols] - dK_ref).max() <= hp.REL_TOL * np.abs(to64(dk[0, :, g])).max()
-    assert np.abs(to64(dv[0, :, g])[cols] - dV_ref).max() <= hp.REL_TOL * np.abs(to64(dv[0, :, g])).max()
+    seen_by = vis_c.sum(axis=0) * 8
+    _assert_close(to64(dk[0, :, g])[cols], dK_ref, seen_by, "dK")
+    _assert_close(to64(dv[0, :, g])[cols], dV_ref, seen_by, "dV")
