@@ -19,6 +19,10 @@
  *     contiguous and strides in elements.  4-D tensor pointers must be 16-byte aligned and their
  *     strides multiples of 8 elements (bf16) or 4 elements (fp32), stride_s at most 2^24 elements
  *     (BURST_ERR_UNSUPPORTED beyond); row vectors need only their natural 4-byte alignment.
+ *     Tensors and row vectors that a call WRITES must not map two elements to one address: taking
+ *     their dimensions of extent > 1 by increasing stride, every stride must cover the span of the
+ *     dimensions before it (BURST_ERR_INVALID_ARG otherwise).  Inputs may overlap (a stride of 0
+ *     broadcasts a head or a batch entry).
  *   - q, k, v, dO are bfloat16.  Accumulation, softmax, lse and D are fp32.
  *   - head_dim is 64 or 128; q_heads must be a multiple of kv_heads; query head h uses key/value
  *     head h / (q_heads / kv_heads).  sq and sk may be any non-negative number (ragged tails and
@@ -172,33 +176,8 @@ int burst_attn_fill_striped_mask(int32_t dev_i, int32_t shard_j, int32_t G, int6
 /* Number of visible (query row, key row) pairs of a step per (batch, head): the benchmark's work
  * unit (4*head_dim flop forward, 10*head_dim backward).  Returns -1 on an invalid mask.  The
  * count is that of the mode and window alone: block_mask lives in device memory and is not read
- * here (nor by the two tile diagnostics below). */
+ * here. */
 int64_t burst_attn_visible_pairs(const burst_mask_t* mask);
-
-/* Host diagnostics of the tile-level mask logic, running the very code the kernels compile (no GPU
- * involved), so that tests can hold it against a brute-force visibility matrix.
- *
- * burst_attn_tile_class: class of the block of query rows [q0, q1) against key rows [k0, k1):
- * 0 = no pair visible (the kernels skip the tile), 1 = every pair visible (no per-element predicate),
- * 2 = mixed.  method 0: the direct position-range test; 1: the per-segment row thresholds the
- * key-stationary kernel derives once for a fixed key range; 2: the same for a fixed query range
- * (query-stationary kernels).  All three must agree.  Negative burst_status_t on a bad argument.
- *
- * burst_attn_visible_tile_runs: the tiles of `tile_rows` rows along the query axis (query_axis != 0;
- * tile_rows 64 or 256) or the key axis (tile_rows 64 or 128) that can hold a pair visible to rows
- * [r0, r1) of the other axis, as at most two runs: out = {start0, len0, start1, len1} in tiles. */
-int burst_attn_tile_class(const burst_mask_t* mask, int64_t q0, int64_t q1, int64_t k0, int64_t k1, int32_t method);
-int burst_attn_visible_tile_runs(const burst_mask_t* mask, int32_t query_axis, int32_t tile_rows, int64_t r0, int64_t r1,
-                                 int32_t out_start_len[4]);
-
-/* Diagnostic, not part of the attention path: enqueues `iterations` x 4 independent bf16 32x32x16
- * MFMAs per wave on every SIMD (512 work-groups of 256 threads) with constant (0) or pseudo-random
- * (1) register operands, and stores the flop count of the launch in *flops_out (host, optional).
- * Timed by the caller with events, it gives the matrix-core ceiling of the chip as it is clocked under
- * that load: dense attention tiles are bounded by the random-operand figure.  sink: optional device
- * pointer to 4 bytes (never written in practice).  iterations in [1, 2^24]. */
-int burst_attn_mfma_probe(int32_t random_operands, int32_t iterations, float* sink, int64_t* flops_out,
-                          void* hip_stream);
 
 const char* burst_attn_status_string(int status);
 int burst_attn_last_hip_error(void);

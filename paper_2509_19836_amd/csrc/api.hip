@@ -1,11 +1,13 @@
 // C-ABI layer of libburstattn: argument validation, host-side mask helpers and kernel dispatch.
 // Every check runs on the host before anything is enqueued.
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <mutex>
 
 #include "../../include/burst_attn.h"
+#include "../../include/burst_attn_diag.h"
 #include "../../include/burst_lm_head.h"
 #include "kernels.hpp"
 
@@ -51,6 +53,42 @@ int check_tensor(const burst_tensor_t* t, int want_dtype_mask /* bit0 bf16 ok, b
   return BURST_OK;
 }
 
+// An output tensor must not map two of its elements to one address: work-groups that own different
+// rows or heads would then write (or read-modify-write) the same memory.  Sufficient test: walking the
+// dimensions of extent > 1 by increasing stride, each stride covers the span of the ones before it.
+// Inputs may overlap (a stride of 0 broadcasts a head or a batch entry), so they are not tested.
+int check_no_overlap(const TensorDev& t, int64_t batch, int64_t rows, int64_t heads, int64_t head_dim) {
+  int64_t stride[3] = {t.sh, t.ss, t.sb}, extent[3] = {heads, rows, batch};
+  for (int a = 0; a < 3; ++a)
+    for (int b = a + 1; b < 3; ++b)
+      if (stride[b] < stride[a]) {
+        std::swap(stride[a], stride[b]);
+        std::swap(extent[a], extent[b]);
+      }
+  int64_t span = head_dim;   // elements covered so far, innermost dimension first
+  for (int a = 0; a < 3; ++a) {
+    if (extent[a] <= 1) continue;
+    if (stride[a] < span) return BURST_ERR_INVALID_ARG;
+    span = stride[a] * (extent[a] - 1) + span;
+  }
+  return BURST_OK;
+}
+
+int check_rowvec_no_overlap(const RowvecDev& t, int64_t batch, int64_t heads, int64_t rows) {
+  int64_t lo = t.sh, lo_n = heads, hi = t.sb, hi_n = batch;
+  if (hi < lo) {
+    std::swap(lo, hi);
+    std::swap(lo_n, hi_n);
+  }
+  int64_t span = rows;
+  if (lo_n > 1) {
+    if (lo < span) return BURST_ERR_INVALID_ARG;
+    span = lo * (lo_n - 1) + span;
+  }
+  if (hi_n > 1 && hi < span) return BURST_ERR_INVALID_ARG;
+  return BURST_OK;
+}
+
 int check_rowvec(const burst_rowvec_t* t, RowvecDev* out) {
   if (!t || !t->ptr) return BURST_ERR_INVALID_ARG;
   if (((uintptr_t)t->ptr) & 3) return BURST_ERR_INVALID_ARG;
@@ -75,6 +113,8 @@ int check_mask(const burst_mask_t* m, int64_t sq, int64_t sk, MaskDev* out) {
   if (m->mode != BURST_MASK_FULL && m->mode != BURST_MASK_CAUSAL) return BURST_ERR_INVALID_ARG;
   if (m->q_nseg < 1 || m->q_nseg > 2 || m->k_nseg < 1 || m->k_nseg > 2) return BURST_ERR_INVALID_ARG;
   if (m->q_seg_len < 0 || m->k_seg_len < 0 || m->pos_stride < 1) return BURST_ERR_INVALID_ARG;
+  // bounded before it is multiplied below (the products then stay far inside int64)
+  if (m->pos_stride > kMaxPos || m->q_seg_len > kMaxRows || m->k_seg_len > kMaxRows) return BURST_ERR_UNSUPPORTED;
   if (m->window < 0 || (m->window > 0 && m->mode != BURST_MASK_CAUSAL)) return BURST_ERR_INVALID_ARG;
   if (m->q_seg_len * m->q_nseg != sq || m->k_seg_len * m->k_nseg != sk) return BURST_ERR_INVALID_ARG;
   for (int s = 0; s < 2; ++s) {
@@ -164,10 +204,14 @@ int burst_attn_step_fwd(const burst_shape_t* shape, const burst_mask_t* mask, co
   if (want_part) {
     BURST_TRY(check_tensor(o_part, 3, &p.o_part));
     BURST_TRY(check_rowvec(lse_part, &p.lse_part));
+    BURST_TRY(check_no_overlap(p.o_part, shape->batch, shape->sq, shape->q_heads, shape->head_dim));
+    BURST_TRY(check_rowvec_no_overlap(p.lse_part, shape->batch, shape->q_heads, shape->sq));
   }
   if (want_acc) {
     BURST_TRY(check_tensor(o_acc, 2, &p.o_acc));
     BURST_TRY(check_rowvec(lse_acc, &p.lse_acc));
+    BURST_TRY(check_no_overlap(p.o_acc, shape->batch, shape->sq, shape->q_heads, shape->head_dim));
+    BURST_TRY(check_rowvec_no_overlap(p.lse_acc, shape->batch, shape->q_heads, shape->sq));
   }
   p.batch = shape->batch;
   p.q_heads = shape->q_heads;
@@ -199,6 +243,9 @@ int burst_attn_lse_merge(const burst_shape_t* shape, const burst_tensor_t* o_acc
   BURST_TRY(check_tensor(o_part, 3, &p.o_part));
   BURST_TRY(check_rowvec(lse_part, &p.lse_part));
   if (o_out_cast) BURST_TRY(check_tensor(o_out_cast, 1, &p.o_out));
+  BURST_TRY(check_no_overlap(p.o_acc, shape->batch, shape->sq, shape->q_heads, shape->head_dim));
+  BURST_TRY(check_rowvec_no_overlap(p.lse_acc, shape->batch, shape->q_heads, shape->sq));
+  if (o_out_cast) BURST_TRY(check_no_overlap(p.o_out, shape->batch, shape->sq, shape->q_heads, shape->head_dim));
   p.batch = shape->batch;
   p.q_heads = shape->q_heads;
   p.head_dim = shape->head_dim;
@@ -216,6 +263,7 @@ int burst_attn_preprocess_bwd(const burst_shape_t* shape, const burst_tensor_t* 
   BURST_TRY(check_tensor(o, 3, &p.o));
   BURST_TRY(check_tensor(d_o, 1, &p.d_o));
   BURST_TRY(check_rowvec(d_out, &p.d));
+  BURST_TRY(check_rowvec_no_overlap(p.d, shape->batch, shape->q_heads, shape->sq));
   p.batch = shape->batch;
   p.q_heads = shape->q_heads;
   p.head_dim = shape->head_dim;
@@ -243,9 +291,18 @@ int burst_attn_step_bwd(const burst_shape_t* shape, const burst_mask_t* mask, co
   if (!dq && !dk && !dv) return BURST_ERR_INVALID_ARG;
   if ((dk == nullptr) != (dv == nullptr)) return BURST_ERR_INVALID_ARG;
   if (accumulate_flags & ~(BURST_ACC_DQ | BURST_ACC_DK | BURST_ACC_DV)) return BURST_ERR_INVALID_ARG;
-  if (dq) BURST_TRY(check_tensor(dq, 2, &p.dq));
-  if (dk) BURST_TRY(check_tensor(dk, 2, &p.dk));
-  if (dv) BURST_TRY(check_tensor(dv, 2, &p.dv));
+  if (dq) {
+    BURST_TRY(check_tensor(dq, 2, &p.dq));
+    BURST_TRY(check_no_overlap(p.dq, shape->batch, shape->sq, shape->q_heads, shape->head_dim));
+  }
+  if (dk) {
+    BURST_TRY(check_tensor(dk, 2, &p.dk));
+    BURST_TRY(check_no_overlap(p.dk, shape->batch, shape->sk, shape->kv_heads, shape->head_dim));
+  }
+  if (dv) {
+    BURST_TRY(check_tensor(dv, 2, &p.dv));
+    BURST_TRY(check_no_overlap(p.dv, shape->batch, shape->sk, shape->kv_heads, shape->head_dim));
+  }
   p.acc_dq = (accumulate_flags & BURST_ACC_DQ) != 0;
   p.acc_dk = (accumulate_flags & BURST_ACC_DK) != 0;
   p.acc_dv = (accumulate_flags & BURST_ACC_DV) != 0;

@@ -155,6 +155,46 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert raw.burst_attn_preprocess_bwd(r(ok_shape), r(tf32), r(t), None, None) == INV
 
 
+def test_outputs_that_overlap_and_unbounded_position_strides_are_rejected(lib):
+    """An output descriptor that maps two elements to one address would make work-groups race without
+    a trace: refused on the host (inputs may overlap: a zero stride broadcasts).  A position stride is
+    bounded before it is multiplied with a segment length."""
+    raw = lib.raw()
+    shp = lib.shape(2, 4, 4, 128, 64, 64, 0.1)
+    r = C.byref
+    INV, UNS = lib.BURST_ERR_INVALID_ARG, lib.BURST_ERR_UNSUPPORTED
+    tin = _fake_tensor(lib, strides=(0, 512, 0))                       # input broadcast over batch and heads: fine
+    good = _fake_tensor(lib, dtype=1, strides=(64 * 512, 512, 128))     # [B, S, H, D] packed
+    heads_first = _fake_tensor(lib, dtype=1, strides=(4 * 64 * 128, 128, 64 * 128))   # [B, H, S, D] described by strides
+    rv = lib.burst_rowvec_t(0x20000, 4 * 64, 64)
+
+    def fwd(o_part=good, lse_part=rv, mask=None):
+        return raw.burst_attn_step_fwd(r(shp), None if mask is None else r(mask), r(tin), r(tin), r(tin), r(o_part), r(lse_part),
+                                       None, None, None)
+    # (the good descriptors get as far as the launch, which needs a GPU: only refusals are asserted here)
+    for bad in (_fake_tensor(lib, dtype=1, strides=(64 * 512, 512, 64)),        # heads 64 apart, 128 wide
+                _fake_tensor(lib, dtype=1, strides=(64 * 512, 256, 128)),       # rows closer than 4 heads of 128
+                _fake_tensor(lib, dtype=1, strides=(64 * 512, 0, 128)),         # every row on the same address
+                _fake_tensor(lib, dtype=1, strides=(0, 512, 128)),              # both batch entries on the same address
+                _fake_tensor(lib, dtype=1, strides=(4 * 64 * 128, 128, 63 * 128 + 64))):   # [B,H,S,D] with heads too close
+        assert fwd(o_part=bad) == INV
+    assert fwd(lse_part=lib.burst_rowvec_t(0x20000, 4 * 64, 32)) == INV         # heads of 64 rows, 32 apart
+    assert fwd(lse_part=lib.burst_rowvec_t(0x20000, 64, 64)) == INV             # batch entries on top of the heads
+
+    def bwd(dq=good, dk=good, dv=good):
+        return raw.burst_attn_step_bwd(r(shp), None, r(tin), r(tin), r(tin), r(tin), r(rv), r(rv), r(dq), r(dk), r(dv), 0, None)
+    overl = _fake_tensor(lib, dtype=1, strides=(64 * 512, 512, 64))
+    assert bwd(dq=overl) == INV and bwd(dk=overl) == INV and bwd(dv=overl) == INV
+    assert raw.burst_attn_lse_merge(r(shp), r(overl), r(rv), r(good), r(rv), None, None) == INV
+    assert raw.burst_attn_lse_merge(r(shp), r(good), r(rv), r(good), r(rv), r(_fake_tensor(lib, strides=(64 * 512, 512, 64))), None) == INV
+    assert raw.burst_attn_preprocess_bwd(r(shp), r(good), r(tin), r(lib.burst_rowvec_t(0x20000, 4 * 64, 32)), None) == INV
+    # a position stride so large that stride * seg_len would wrap int64
+    m = lib.burst_mask_t(1, 1, 1, 0, (0, 0), (0, 0), 64, 64, (1 << 62) + 1)
+    assert fwd(mask=m) == UNS
+    assert lib.raw().burst_attn_tile_class(r(m), 0, 64, 0, 64, 0) == UNS
+    assert heads_first.stride_h == 64 * 128   # (descriptor kept for the GPU test of the same layout)
+
+
 def test_empty_query_chunk_returns_ok_without_a_launch(lib):
     raw = lib.raw()
     t, tf32, rv = _fake_tensor(lib), _fake_tensor(lib, dtype=1), _fake_rowvec(lib)
