@@ -23,10 +23,12 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
 
 # HBM bytes per launch of the dominant kernel from the FETCH_SIZE / WRITE_SIZE counter runs of this
-# command (profiles/bench_config2_pmc_hbm_traffic.md: counter means over the ring, scaled by what the
-# same counters read for the 1 GiB copy issued below).  Counters cannot be read from inside the
-# process, so the figure is the profiled one and exists for the profiled workload only.
-PROFILED_TRAFFIC_BYTES = {2: 1.922e9}
+# command (counter means over the ring, scaled by what the same counters read for the 1 GiB copy issued
+# below).  Counters cannot be read from inside the process, so the figure is the profiled one: it is
+# reported with the profile it came from and its date, and only for the workload that was profiled.
+PROFILED_TRAFFIC = {
+    2: {"bytes": 1.922e9, "profile": "profiles/bench_config2_pmc_hbm_traffic.md", "taken": "round-1 kernels"},
+}
 # --lm-head, default shape: bytes per call over all its launches (profiles/bench_lm_head_kernel_trace_and_counters.md)
 PROFILED_LM_HEAD_TRAFFIC_BYTES = 2.73e10
 
@@ -173,45 +175,62 @@ def lm_head_bench(args):
     print(json.dumps(out))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=2, help="workload index (1-5) of the benchmark definition")
-    ap.add_argument("--device-index", type=int, default=3, help="which simulated device's ring to run")
-    ap.add_argument("--cpu-sample-rows", type=int, default=16384)
-    ap.add_argument("--window", type=int, default=0, help="sliding-window attention: window in tokens (0 = none); "
-                                                           "not the headline metric, for the sparse rows")
-    ap.add_argument("--partition", default=None, choices=["zigzag", "striped", "causal", "full"],
-                    help="override the workload's partition / mask kind")
-    ap.add_argument("--block-density", type=float, default=0.0,
-                    help="block-wise sparse attention: fraction of open blocks of a seeded random pattern over "
-                         "global token blocks, diagonal always open (0 = no block mask); not the headline metric")
-    ap.add_argument("--block-rows", type=int, default=512, help="rows of a (square) block of that pattern")
-    ap.add_argument("--cpu-shards", type=int, default=4, help="KV shards the CPU baseline sample covers")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--lm-head", action="store_true", help="measure the fused LM head + loss (Alg. 3) instead of the ring")
-    ap.add_argument("--lm-tokens", type=int, default=16384)
-    ap.add_argument("--vocab", type=int, default=32000, help="--lm-head: vocabulary (32000: LLaMA-1/2, 128256: LLaMA-3)")
-    ap.add_argument("--tile-tokens", type=int, default=8192, help="--lm-head: tokens per sequence tile (B_s)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        sys.exit("bench.py: this build measures the per-device compute step on ONE GPU; the ring is simulated "
-                 "in HBM and there is no multi-GPU path (--gpus must be 1)")
+class ClockSampler:
+    """Shader clock as the kernel driver reports it (the starred level of pp_dpm_sclk in sysfs),
+    sampled from a thread while the timed region runs.  None where the file cannot be read."""
 
-    if args.lm_head:
-        return lm_head_bench(args)
+    def __init__(self, period_s=0.05):
+        import glob
+        import threading
+        self.paths = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        self.period, self.samples, self._stop = period_s, [], threading.Event()
+        self._thread = threading.Thread(target=self._run, daemon=True)
+
+    def _read(self):
+        best = None
+        for path in self.paths:
+            try:
+                for line in open(path).read().splitlines():
+                    if line.rstrip().endswith("*"):
+                        mhz = int("".join(ch for ch in line.split(":")[1] if ch.isdigit()))
+                        best = mhz if best is None else max(best, mhz)
+            except (OSError, ValueError, IndexError):
+                pass
+        return best
+
+    def _run(self):
+        while not self._stop.is_set():
+            v = self._read()
+            if v is not None:
+                self.samples.append(v)
+            self._stop.wait(self.period)
+
+    def __enter__(self):
+        self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        self._thread.join()
+
+    def summary(self):
+        if not self.samples:
+            return None
+        xs = sorted(self.samples)
+        return {"source": "pp_dpm_sclk (sysfs), current level", "samples": len(xs), "min": xs[0],
+                "median": xs[len(xs) // 2], "max": xs[-1]}
+
+
+def run_ring(args, config, steps, warmup, sample_clock=False):
+    """Device i's whole simulated ring of one workload, `steps` times; returns the measurements."""
     import torch
     from paper_2509_19836_amd import binding as lib, ring, workloads as wl
-    assert torch.cuda.is_available(), "bench.py needs the GPU"
-    torch.cuda.set_device(0)
-    w = wl.WORKLOADS[args.config]
+    w = wl.WORKLOADS[config]
     kind, G, N, i = args.partition or w.mask, w.shards, w.seq, args.device_index % w.shards
     n, d, B, Hq, Hkv = w.shard_tokens, w.head_dim, w.batch, w.q_heads, w.kv_heads
 
     gen = torch.Generator(device="cuda")
-    gen.manual_seed(wl.BASE_SEED + 100 * args.config)
+    gen.manual_seed(wl.BASE_SEED + 100 * config)
 
     def draw(heads):
         x = torch.randn(B, n, heads, d, device="cuda", dtype=torch.float32, generator=gen)
@@ -281,15 +300,20 @@ def main():
     # The running state and the gradient accumulators are initialised once; later rings keep
     # folding into them ("+=" and merge are the same work whatever the buffers hold).
     reset()
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         one_ring(False)
     all_marks = []
+    sampler = ClockSampler() if sample_clock else None
     torch.cuda.synchronize()
+    if sampler:
+        sampler.__enter__()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         all_marks += one_ring(True)
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t0
+    if sampler:
+        sampler.__exit__()
     for name, j, a, b in all_marks:
         ms = a.elapsed_time(b)
         spans[name].append(ms)
@@ -297,38 +321,27 @@ def main():
             by_kind.setdefault((name, kind_of(j)), []).append(ms)
     assert torch.isfinite(o_acc).all() and torch.isfinite(dq).all(), "non-finite result"
 
-    # Outside the timed region: (1) the matrix-core ceiling of this chip as clocked under load, with
-    # constant and with random register operands (real attention tiles are bounded by the latter: the
-    # chip lowers its clock when the MFMA inputs toggle); (2) one plain 1 GiB device copy, so that a
-    # counter profile of this command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by.
-    ceiling = {}
-    for name, rnd in (("constant_operands", 0), ("random_operands", 1)):
-        lib.burst_attn_mfma_probe(rnd, 20000)
-        a, b = ev(), ev()
-        a.record()
-        flops = lib.burst_attn_mfma_probe(rnd, 200000)
-        b.record()
-        torch.cuda.synchronize()
-        ceiling[name] = flops / (a.elapsed_time(b) * 1e-3) / 1e12
-    src = torch.empty(1 << 28, device="cuda", dtype=torch.float32)
-    dst = torch.empty_like(src)
-    dst.copy_(src)
+    # Outside the timed region: the standalone online-softmax merge (bound by HBM: it reads the running
+    # O, reads the partial, writes the running O, all fp32), timed on this workload's buffers.
+    o_part = torch.zeros(B, n, Hq, d, **f32)
+    lse_part = torch.zeros(B, Hq, n, **f32)
+    merge = lambda: lib.burst_attn_lse_merge(shp, o_acc, lse_acc, o_part, lse_part)
+    merge()
+    a, b = ev(), ev()
+    a.record()
+    for _ in range(5):
+        merge()
+    b.record()
     torch.cuda.synchronize()
-    del src, dst
+    merge_ms = a.elapsed_time(b) / 5
+    merge_bytes = B * n * Hq * (3 * d * 4 + 3 * 4)
+    del o_part, lse_part
 
     ring_pairs = sum(pairs.values()) * B * Hq
     fl_fwd, fl_bwd = ring_pairs * 4 * d, ring_pairs * 10 * d
-    ms_ring = total_s / args.steps * 1e3
+    ms_ring = total_s / steps * 1e3
     avg = {k: sum(v) / len(v) for k, v in spans.items() if v}
     fwd_ms, bwd_ms = avg["step_fwd"] * G, (avg["step_bwd_dq"] + avg["step_bwd_dkdv"]) * G
-    value = (fl_fwd + fl_bwd) / (ms_ring * 1e-3) / 1e12
-
-    # roofline of the dominant kernel (key-stationary dK/dV kernel).  Of the 10 d flop per visible
-    # pair of a backward step it is charged 6 d: dV (2 d), dK (2 d) and half of the S and dP GEMMs
-    # (2 d) that both backward kernels recompute; the dQ kernel carries the other 4 d.
-    per_launch_pairs = sum(pairs.values()) / G * B * Hq
-    dom_flops = per_launch_pairs * 6 * d
-    achieved = dom_flops / (avg["step_bwd_dkdv"] * 1e-3) / 1e12
     # The kinds of ring step timed separately: TFLOPS of a whole step (fwd + dq + dkdv launches) from the
     # median duration of each launch, with that step's own visible-pair count.
     med = lambda v: sorted(v)[len(v) // 2]
@@ -346,34 +359,135 @@ def main():
                              "fwd_bwd_tflops": round(step_pairs * 14 * d / ((f_ms + q_ms + kv_ms) * 1e-3) / 1e12, 1)}
     # D = rowsum(dO o O) is bound by HBM: it reads O (fp32) and dO (bf16) once and writes one float per row
     pre_bytes = B * n * Hq * (d * 6 + 4)
+    return {
+        "workload": w, "kind": kind, "device": i, "order": order, "pattern": pattern,
+        "name": f"{w.name} (config {config}): device {i} of {G}, one full simulated ring = "
+                f"{G} fwd steps + D + {G} bwd steps, B={B} Hq={Hq} Hkv={Hkv} d={d}, "
+                f"Q chunk {n} x {G} KV chunks of {n}, mask {kind}" + (f", window {args.window}" if args.window else "")
+                + (f", block-sparse pattern of density {args.block_density} over {args.block_rows}-token blocks"
+                   if pattern is not None else ""),
+        "value": (fl_fwd + fl_bwd) / (ms_ring * 1e-3) / 1e12, "ms_ring": ms_ring,
+        "fwd_tflops": fl_fwd / (fwd_ms * 1e-3) / 1e12, "bwd_tflops": fl_bwd / (bwd_ms * 1e-3) / 1e12,
+        "avg": avg, "min": {k: min(v) for k, v in spans.items() if v}, "step_kinds": step_kinds,
+        "preprocess_bwd_gb_s": pre_bytes / (avg["preprocess_bwd"] * 1e-3) / 1e9,
+        "lse_merge_gb_s": merge_bytes / (merge_ms * 1e-3) / 1e9, "lse_merge_ms": merge_ms,
+        "per_launch_pairs": sum(pairs.values()) / G * B * Hq,
+        "clock": sampler.summary() if sampler else None,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=5,
+                    help="workload index (1-5) of the benchmark definition; 5 = the 128K-token-shard configuration "
+                         "the target is stated on (1M tokens over 8 shards), also the largest that one GPU holds")
+    ap.add_argument("--device-index", type=int, default=3, help="which simulated device's ring to run")
+    ap.add_argument("--cpu-sample-rows", type=int, default=0,
+                    help="query rows of the CPU-oracle sample (0: sized so that the sample holds about 5e8 pairs)")
+    ap.add_argument("--window", type=int, default=0, help="sliding-window attention: window in tokens (0 = none); "
+                                                           "not the headline metric, for the sparse rows")
+    ap.add_argument("--partition", default=None, choices=["zigzag", "striped", "causal", "full"],
+                    help="override the workload's partition / mask kind")
+    ap.add_argument("--block-density", type=float, default=0.0,
+                    help="block-wise sparse attention: fraction of open blocks of a seeded random pattern over "
+                         "global token blocks, diagonal always open (0 = no block mask); not the headline metric")
+    ap.add_argument("--block-rows", type=int, default=512, help="rows of a (square) block of that pattern")
+    ap.add_argument("--cpu-shards", type=int, default=0, help="KV shards the CPU baseline sample covers (0: 2 for shards "
+                                                              "of 65536 rows or more, else 4)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-config2", action="store_true", help="skip the extra (untimed for the headline) config-2 ring")
+    ap.add_argument("--lm-head", action="store_true", help="measure the fused LM head + loss (Alg. 3) instead of the ring")
+    ap.add_argument("--lm-tokens", type=int, default=16384)
+    ap.add_argument("--vocab", type=int, default=32000, help="--lm-head: vocabulary (32000: LLaMA-1/2, 128256: LLaMA-3)")
+    ap.add_argument("--tile-tokens", type=int, default=8192, help="--lm-head: tokens per sequence tile (B_s)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build measures the per-device compute step on ONE GPU; the ring is simulated "
+                 "in HBM and there is no multi-GPU path (--gpus must be 1)")
+
+    if args.lm_head:
+        return lm_head_bench(args)
+    import torch
+    from paper_2509_19836_amd import binding as lib, workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    m = run_ring(args, args.config, args.steps, args.warmup, sample_clock=True)
+    w, d = m["workload"], m["workload"].head_dim
+    torch.cuda.empty_cache()
+    # The previous headline workload (config 2, 16384-token shards), so that rounds stay comparable: its own
+    # timed rings, after the headline's region and outside it.
+    extra = None
+    plain = not args.window and not args.partition and m["pattern"] is None
+    if args.config != 2 and not args.no_config2 and plain:
+        m2 = run_ring(args, 2, 10, 2)
+        extra = {"fwd_bwd_tflops": round(m2["value"], 2), "fwd_tflops": round(m2["fwd_tflops"], 2),
+                 "bwd_tflops": round(m2["bwd_tflops"], 2), "ms_per_ring": round(m2["ms_ring"], 3), "rings_timed": 10,
+                 "kernel_ms": {k: round(v, 4) for k, v in m2["avg"].items()}}
+        torch.cuda.empty_cache()
+
+    # Outside the timed region: (1) the matrix-core ceiling of this chip as clocked under load, with
+    # constant and with random register operands (real attention tiles are bounded by the latter: the
+    # chip lowers its clock when the MFMA inputs toggle); (2) one plain 1 GiB device copy, so that a
+    # counter profile of this command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by.
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    ceiling = {}
+    for name, rnd in (("constant_operands", 0), ("random_operands", 1)):
+        lib.burst_attn_mfma_probe(rnd, 20000)
+        a, b = ev(), ev()
+        a.record()
+        flops = lib.burst_attn_mfma_probe(rnd, 200000)
+        b.record()
+        torch.cuda.synchronize()
+        ceiling[name] = flops / (a.elapsed_time(b) * 1e-3) / 1e12
+    src = torch.empty(1 << 28, device="cuda", dtype=torch.float32)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+    # roofline of the dominant kernel (key-stationary dK/dV kernel).  Of the 10 d flop per visible
+    # pair of a backward step it is charged 6 d: dV (2 d), dK (2 d) and half of the S and dP GEMMs
+    # (2 d) that both backward kernels recompute; the dQ kernel carries the other 4 d.
+    avg, value = m["avg"], m["value"]
+    dom_flops = m["per_launch_pairs"] * 6 * d
+    achieved = dom_flops / (avg["step_bwd_dkdv"] * 1e-3) / 1e12
+    profiled = PROFILED_TRAFFIC.get(args.config) if (m["device"] == 3 and plain) else None
     out = {
         "metric": "attention fwd+bwd TFLOPS per ring step (unmasked FLOPs)",
         "value": round(value, 2), "unit": "TFLOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_ring, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(m["ms_ring"], 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{w.name} (config {args.config}): device {i} of {G}, one full simulated ring = "
-                               f"{G} fwd steps + D + {G} bwd steps, B={B} Hq={Hq} Hkv={Hkv} d={d}, "
-                               f"Q chunk {n} x {G} KV chunks of {n}, mask {kind}" + (f", window {args.window}" if args.window else "")
-                               + (f", block-sparse pattern of density {args.block_density} over {args.block_rows}-token blocks"
-                                  if pattern is not None else ""),
-                   "ring_steps_per_step": G, "ms_per_ring_step": round(ms_ring / G, 3)},
+        "config": {"workload": m["name"], "ring_steps_per_step": w.shards,
+                   "ms_per_ring_step": round(m["ms_ring"] / w.shards, 3)},
         "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
-        "fwd_tflops": round(fl_fwd / (fwd_ms * 1e-3) / 1e12, 2),
-        "bwd_tflops": round(fl_bwd / (bwd_ms * 1e-3) / 1e12, 2),
+        "fwd_tflops": round(m["fwd_tflops"], 2),
+        "bwd_tflops": round(m["bwd_tflops"], 2),
         "kernel_ms": {k: round(v, 4) for k, v in avg.items()},
-        "kernel_ms_min": {k: round(min(v), 4) for k, v in spans.items() if v},
-        "step_kinds": step_kinds,
-        "preprocess_bwd_gb_s": round(pre_bytes / (avg["preprocess_bwd"] * 1e-3) / 1e9, 1),
+        "kernel_ms_min": {k: round(v, 4) for k, v in m["min"].items()},
+        "step_kinds": m["step_kinds"],
+        "preprocess_bwd_gb_s": round(m["preprocess_bwd_gb_s"], 1),
+        "lse_merge_gb_s": round(m["lse_merge_gb_s"], 1),
+        "hbm_peak_gb_s": 8000.0,
+        "shader_clock_mhz": m["clock"],
         "mfma_ceiling_tflops": {k: round(v, 1) for k, v in ceiling.items()},
         "pct_of_random_operand_mfma_ceiling": round(100 * value / ceiling["random_operands"], 2),
+        "config2_llama7b_zigzag_128k": extra,
         "roofline": {"bound": "mfma", "kernel": "step_bwd_dkdv_kernel", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": PROFILED_TRAFFIC_BYTES.get(args.config) if (i == 3 and not args.window and not args.partition and pattern is None) else None,
-                     "issued_tflops": round(per_launch_pairs * 8 * d / (avg["step_bwd_dkdv"] * 1e-3) / 1e12, 2)},
+                     "traffic": profiled["bytes"] if profiled else None,
+                     "traffic_source": {k: profiled[k] for k in ("profile", "taken")} if profiled else None,
+                     "issued_tflops": round(m["per_launch_pairs"] * 8 * d / (avg["step_bwd_dkdv"] * 1e-3) / 1e12, 2)},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, kind, i, order[1:1 + args.cpu_shards] or order[:1], args.cpu_sample_rows,
-                                           wl.BASE_SEED + 5, args.window, pattern, args.block_rows)
+        big = w.shard_tokens >= 65536
+        shards = args.cpu_shards or (2 if big else 4)
+        rows = args.cpu_sample_rows or max(256, min(w.shard_tokens, int(5.4e8 / (0.5 * shards * w.shard_tokens))))
+        order = m["order"]
+        out["cpu_baseline"] = cpu_baseline(w, m["kind"], m["device"], order[1:1 + shards] or order[:1], rows,
+                                           wl.BASE_SEED + 5, args.window, m["pattern"], args.block_rows)
     print(json.dumps(out))
 
 
