@@ -385,6 +385,22 @@ def test_grouped_query_wrappers_against_per_head_loops_and_fd():
     assert np.abs(O - O2).max() < 1e-12 and np.abs(lse - lse2).max() < 1e-12
     Om, lm = oc.mha_lse_merge(np.zeros_like(O), np.full(lse.shape, -np.inf), O2, lse2)
     assert (Om == O2).all() and (lm == lse2).all()
+    # a running state that is not trivial: the keys split in two halves, each head with its own state,
+    # merged head by head must give back the unsharded result (a wrong head index on either side of
+    # the merge mixes heads whose states differ, and fails)
+    half = S // 2
+    Oa, la = oc.mha_step_fwd(Q, K[:, :half], V[:, :half], scale, vis[:, :half])
+    Ob, lb = oc.mha_step_fwd(Q, K[:, half:], V[:, half:], scale, vis[:, half:])
+    assert np.abs(la[0, 0] - la[0, 1]).max() > 1e-3 and np.abs(Oa[:, :, 0] - Oa[:, :, 2]).max() > 1e-3
+    Om, lm = oc.mha_lse_merge(Oa, la, Ob, lb)
+    assert np.abs(Om - O).max() < 1e-12 and np.abs(lm - lse).max() < 1e-12
+    Om2, lm2 = oc.mha_lse_merge(Ob, lb, Oa, la)     # the merge commutes
+    assert np.abs(Om2 - O).max() < 1e-12 and np.abs(lm2 - lse).max() < 1e-12
+    # written out for one (batch, head, row): weights e^(lse - lse') on each side
+    b_, h_, r_ = 0, 3, S - 1
+    lnew = np.log(np.exp(la[b_, h_, r_]) + np.exp(lb[b_, h_, r_]))
+    want = np.exp(la[b_, h_, r_] - lnew) * Oa[b_, r_, h_] + np.exp(lb[b_, h_, r_] - lnew) * Ob[b_, r_, h_]
+    assert np.abs(Om[b_, r_, h_] - want).max() < 1e-12 and abs(lm[b_, h_, r_] - lnew) < 1e-12
 
 
 # ----------------------------------------------------------------- independent library routine
