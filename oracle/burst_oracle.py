@@ -57,6 +57,31 @@ def striped_positions(i, G, N):
     return np.arange(i, N, G, dtype=np.int64)
 
 
+def block_striped_positions(i, G, N, N_blk):
+    """Block-striped split for block-wise sparse attention (Sec. 3.4, "a strategy similar to
+    striped-way workload balance", drawn only in a figure): the sequence is cut into blocks of N_blk
+    tokens, N_blk a multiple of G, and every block is dealt to the G devices in G slices of
+    N_blk/G consecutive tokens; device i holds slice i of every block, blocks in order.  Every device
+    then holds the same number of tokens of every block.  (The other way to deal a block out, token
+    i + G*m of every block to device i, is the striped split of Eq. 13 itself, because N_blk is a
+    multiple of G: striped_positions.)"""
+    if N % N_blk or N_blk % G:
+        raise ValueError("N must be a multiple of N_blk and N_blk a multiple of G")
+    m = N_blk // G
+    starts = np.arange(0, N, N_blk, dtype=np.int64) + i * m
+    return (starts[:, None] + np.arange(m, dtype=np.int64)[None, :]).reshape(-1)
+
+
+def block_pattern_visibility(pos_q, pos_k, pattern, N_blk):
+    """Block-wise sparse attention by its definition (Sec. 3.4): with the sequence cut into blocks
+    of N_blk tokens, the token at global position p may attend to the token at position p' iff
+    M_blk[p // N_blk, p' // N_blk] = 1."""
+    pos_q = np.asarray(pos_q, dtype=np.int64)
+    pos_k = np.asarray(pos_k, dtype=np.int64)
+    pattern = np.asarray(pattern)
+    return pattern[(pos_q // N_blk)[:, None], (pos_k // N_blk)[None, :]] != 0
+
+
 def visibility(pos_q, pos_k, causal, window=0):
     """Boolean [len(pos_q), len(pos_k)]: may query row r use key row c?
     Causal (Eq. 10): a token attends to keys 1..i, itself included.

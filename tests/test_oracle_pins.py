@@ -563,6 +563,73 @@ def test_block_sparse_ring_equals_unsharded():
     assert not np.isfinite(lse_ref[2 * blk:3 * blk]).any() and (O_ref[2 * blk:3 * blk] == 0).all()
 
 
+@pytest.mark.parametrize("G,N,N_blk", [(2, 48, 8), (4, 96, 16), (3, 54, 18)])
+def test_block_striped_split_covers_once_and_slices_every_block(G, N, N_blk):
+    """Sec. 3.4, block-wise sparse attention: every device holds the same number of tokens of every
+    block, and the devices together hold every token once.  Written out by loops, not via the oracle."""
+    m = N_blk // G
+    seen = np.zeros(N, int)
+    for i in range(G):
+        pos = oc.block_striped_positions(i, G, N, N_blk)
+        want = [b * N_blk + i * m + t for b in range(N // N_blk) for t in range(m)]
+        assert pos.tolist() == want
+        assert (np.diff(pos) > 0).all()                       # local row order is position order
+        seen[pos] += 1
+        for b in range(N // N_blk):
+            assert ((pos // N_blk) == b).sum() == m
+        # local row block a of m rows lies inside global block a: the step's block mask is M_blk itself
+        assert ((pos // N_blk) == np.arange(pos.size) // m).all()
+        # the same holds for the striped split of Eq. 13 (tokens i + G*t), the other way to deal out a block
+        spos = oc.striped_positions(i, G, N)
+        assert ((spos // N_blk) == np.arange(spos.size) // m).all()
+    assert (seen == 1).all()
+    with pytest.raises(ValueError):
+        oc.block_striped_positions(0, G, N, N_blk + 1)
+
+
+@pytest.mark.parametrize("split", ["block_striped", "striped"])
+def test_block_sparse_steps_are_balanced_and_ring_equals_unsharded(split):
+    """Under either way of dealing blocks out, (1) the step's visibility by the definition on global
+    positions equals the global pattern applied to LOCAL row blocks of N_blk/G rows, (2) every step
+    of every device has the same number of visible pairs under a pure block pattern ("exactly the
+    same compute workload"), and (3) ring + merge over the steps gives unsharded block-sparse
+    attention, also with the causal rule and a window on top."""
+    G, N, N_blk, d, scale = 3, 72, 12, 4, 0.5
+    m = N_blk // G
+    r = rng(84)
+    Q, K, V, dO = rand_qkvdo(85, N, N, d)
+    Mg = (r.random((N // N_blk, N // N_blk)) < 0.5).astype(np.uint8)
+    np.fill_diagonal(Mg, 1)
+    pos_of = (lambda i: oc.block_striped_positions(i, G, N, N_blk)) if split == "block_striped" else \
+             (lambda i: oc.striped_positions(i, G, N))
+    glob = np.arange(N)
+    counts = set()
+    for causal, window in ((False, 0), (True, 0), (True, 20)):
+        vis_all = oc.block_pattern_visibility(glob, glob, Mg, N_blk) & oc.visibility(glob, glob, causal, window)
+        O_ref, lse_ref = oc.attention_fwd(Q, K, V, scale, vis_all)
+        ring_pairs = []
+        for i in range(G):
+            pos_i = pos_of(i)
+            def vis_of(j):
+                pos_j = pos_of(j)
+                by_definition = oc.block_pattern_visibility(pos_i, pos_j, Mg, N_blk) & oc.visibility(pos_i, pos_j, causal, window)
+                local = oc.apply_block_mask(oc.visibility(pos_i, pos_j, causal, window), Mg, m, m)
+                assert (by_definition == local).all()
+                return local
+            if not causal:
+                for j in range(G):
+                    counts.add(int(vis_of(j).sum()))
+            ring_pairs.append(sum(int(vis_of(j).sum()) for j in range(G)))
+            O_i, lse_i = oc.ring_fwd(Q[pos_i], [K[pos_of(j)] for j in range(G)], [V[pos_of(j)] for j in range(G)], scale,
+                                     vis_of, oc.ring_order(i, G))
+            assert np.abs(O_i - O_ref[pos_i]).max() < 1e-12
+            assert np.abs(lse_i - lse_ref[pos_i]).max() < 1e-12
+        if causal and not window and split == "striped":
+            # token stripes stay balanced under the causal rule as well: devices differ by O(rows), not O(rows^2)
+            assert max(ring_pairs) - min(ring_pairs) <= (N // N_blk) * m * G
+    assert counts == {int(Mg.sum()) * m * m}
+
+
 # ----------------------------------------------------------------- planted mistakes are caught
 
 def test_planted_mistakes_fail_the_pins(monkeypatch):
