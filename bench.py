@@ -34,22 +34,23 @@ PROFILED_LM_HEAD_TRAFFIC_BYTES = 2.73e10
 
 
 def block_masked_pairs(bm, pos_q, pos_k, R, causal, window):
-    """Visible pairs of a step under a local block mask: per open block pair, the pairs that the
-    mode and the window leave, a function of the offset between the two blocks' first positions."""
+    """Visible pairs of a step under a local block mask (blocks of R local rows): per open block pair,
+    the pairs that the mode and the window leave; a function of the offset between the two blocks' first
+    positions, since every local block has the same position pattern (consecutive or G apart)."""
     import numpy as np
     memo, total = {}, 0
-    ar = np.arange(R)
+    rel_q, rel_k = pos_q[:R] - pos_q[0], pos_k[:R] - pos_k[0]
     for a, b in zip(*np.nonzero(bm)):
         off = int(pos_q[a * R] - pos_k[b * R])
         if off not in memo:
-            diff = off + ar[:, None] - ar[None, :]
+            diff = off + rel_q[:, None] - rel_k[None, :]
             ok = np.ones_like(diff, dtype=bool) if not causal else (diff >= 0) & ((diff < window) if window else True)
             memo[off] = int(ok.sum())
         total += memo[off]
     return total
 
 
-def cpu_baseline(w, kind, dev_i, shards, sample_rows, seed, window=0, pattern=None, block_rows=0):
+def cpu_baseline(w, kind, dev_i, shards, sample_rows, seed, window=0, pattern=None, block_rows=0, block_tokens=0):
     """The fp64 oracle, untuned, on a bounded sample of the same workload: `sample_rows` query rows
     (evenly spaced over the chunk) of one (batch, head) against each of the whole KV shards in
     `shards`, forward step + D + backward step per shard.  Returns TFLOPS with the same
@@ -59,7 +60,8 @@ def cpu_baseline(w, kind, dev_i, shards, sample_rows, seed, window=0, pattern=No
     from paper_2509_19836_amd import workloads as wl
     G, N, d = w.shards, w.seq, w.head_dim
     pos_fn = {"zigzag": oc.zigzag_positions, "full": oc.contiguous_positions, "causal": oc.contiguous_positions,
-              "striped": oc.striped_positions}[kind]
+              "striped": oc.striped_positions,
+              "block_striped": lambda i_, G_, N_: oc.block_striped_positions(i_, G_, N_, block_tokens)}[kind]
     qpos_all = pos_fn(dev_i, G, N)
     sel = np.linspace(0, qpos_all.size - 1, sample_rows).astype(np.int64)
     rng = np.random.Generator(np.random.PCG64(seed))
@@ -72,8 +74,9 @@ def cpu_baseline(w, kind, dev_i, shards, sample_rows, seed, window=0, pattern=No
         if pattern is None:
             vis = oc.visibility(qpos_all[sel], kpos, kind != "full", window)
         else:
-            bm = wl.local_block_mask(pattern, qpos_all, kpos, block_rows)
-            vis = oc.apply_block_mask(oc.visibility(qpos_all, kpos, kind != "full", window), bm, block_rows, block_rows)[sel]
+            R = block_rows // G if kind in ("striped", "block_striped") else block_rows
+            bm = wl.local_block_mask(pattern, qpos_all, kpos, R, block_rows)
+            vis = oc.apply_block_mask(oc.visibility(qpos_all, kpos, kind != "full", window), bm, R, R)[sel]
         pairs += int(vis.sum())
         t0 = time.perf_counter()
         O, lse = oc.step_fwd(Q, K, V, w.scale, vis)
@@ -249,17 +252,21 @@ def run_ring(args, config, steps, warmup, sample_clock=False):
     dvs = [torch.empty(B, n, Hkv, d, **f32) for _ in range(G)]
 
     order = ring.ring_order(i, G)
-    masks = {j: ring.fill_mask(kind, i, j, G, N, args.window) for j in order}
+    block_tokens = args.block_rows if args.block_density > 0 else args.block_tokens   # N_blk of the block-striped split
+    masks = {j: ring.fill_mask(kind, i, j, G, N, args.window, block_tokens) for j in order}
     pairs = {j: lib.burst_attn_visible_pairs(masks[j]) for j in order}
     pattern, block_masks = None, []
     if args.block_density > 0:
-        if kind == "striped":
-            sys.exit("bench.py: a pattern over blocks of consecutive tokens does not map to row blocks of the striped split")
-        R = args.block_rows
-        pattern = wl.block_sparse_pattern(N // R, args.block_density, wl.BASE_SEED + 77)
+        # global blocks of --block-rows tokens; a local row block is a whole global block under the splits that
+        # keep consecutive tokens together, slice / stripe i of it (1/G of its rows) under the two balanced splits
+        Rg = args.block_rows
+        R = Rg // G if kind in ("striped", "block_striped") else Rg
+        if R % 256:
+            sys.exit(f"bench.py: local row blocks of {R} rows; the kernels need multiples of 256 (raise --block-rows)")
+        pattern = wl.block_sparse_pattern(N // Rg, args.block_density, wl.BASE_SEED + 77)
         for j in order:
             pos_q, pos_k = ring.mask_positions(masks[j], "q"), ring.mask_positions(masks[j], "k")
-            bm = wl.local_block_mask(pattern, pos_q, pos_k, R)
+            bm = wl.local_block_mask(pattern, pos_q, pos_k, R, Rg)
             block_masks.append(torch.from_numpy(bm).cuda())   # kept alive for the whole run
             lib.set_block_mask(masks[j], block_masks[-1], R, R)
             pairs[j] = block_masked_pairs(bm, pos_q, pos_k, R, kind != "full", args.window)
@@ -360,10 +367,13 @@ def run_ring(args, config, steps, warmup, sample_clock=False):
     # D = rowsum(dO o O) is bound by HBM: it reads O (fp32) and dO (bf16) once and writes one float per row
     pre_bytes = B * n * Hq * (d * 6 + 4)
     return {
-        "workload": w, "kind": kind, "device": i, "order": order, "pattern": pattern,
+        "workload": w, "kind": kind, "device": i, "order": order, "pattern": pattern, "block_tokens": block_tokens,
+        "pairs_per_step": {str(j): pairs[j] for j in order},
         "name": f"{w.name} (config {config}): device {i} of {G}, one full simulated ring = "
                 f"{G} fwd steps + D + {G} bwd steps, B={B} Hq={Hq} Hkv={Hkv} d={d}, "
-                f"Q chunk {n} x {G} KV chunks of {n}, mask {kind}" + (f", window {args.window}" if args.window else "")
+                f"Q chunk {n} x {G} KV chunks of {n}, mask {kind}"
+                + (f" (blocks of {block_tokens} tokens)" if kind == "block_striped" else "")
+                + (f", window {args.window}" if args.window else "")
                 + (f", block-sparse pattern of density {args.block_density} over {args.block_rows}-token blocks"
                    if pattern is not None else ""),
         "value": (fl_fwd + fl_bwd) / (ms_ring * 1e-3) / 1e12, "ms_ring": ms_ring,
@@ -389,8 +399,10 @@ def main():
                     help="query rows of the CPU-oracle sample (0: sized so that the sample holds about 5e8 pairs)")
     ap.add_argument("--window", type=int, default=0, help="sliding-window attention: window in tokens (0 = none); "
                                                            "not the headline metric, for the sparse rows")
-    ap.add_argument("--partition", default=None, choices=["zigzag", "striped", "causal", "full"],
-                    help="override the workload's partition / mask kind")
+    ap.add_argument("--partition", default=None, choices=["zigzag", "striped", "block_striped", "causal", "full"],
+                    help="override the workload's partition / mask kind (block_striped: slice i of every block of "
+                         "--block-tokens tokens, the split of block-wise sparse attention)")
+    ap.add_argument("--block-tokens", type=int, default=4096, help="N_blk of --partition block_striped without a block pattern")
     ap.add_argument("--block-density", type=float, default=0.0,
                     help="block-wise sparse attention: fraction of open blocks of a seeded random pattern over "
                          "global token blocks, diagonal always open (0 = no block mask); not the headline metric")
@@ -468,6 +480,7 @@ def main():
         "kernel_ms": {k: round(v, 4) for k, v in avg.items()},
         "kernel_ms_min": {k: round(v, 4) for k, v in m["min"].items()},
         "step_kinds": m["step_kinds"],
+        "visible_pairs_per_ring_step": m["pairs_per_step"],
         "preprocess_bwd_gb_s": round(m["preprocess_bwd_gb_s"], 1),
         "lse_merge_gb_s": round(m["lse_merge_gb_s"], 1),
         "hbm_peak_gb_s": 8000.0,
@@ -487,7 +500,7 @@ def main():
         rows = args.cpu_sample_rows or max(256, min(w.shard_tokens, int(5.4e8 / (0.5 * shards * w.shard_tokens))))
         order = m["order"]
         out["cpu_baseline"] = cpu_baseline(w, m["kind"], m["device"], order[1:1 + shards] or order[:1], rows,
-                                           wl.BASE_SEED + 5, args.window, m["pattern"], args.block_rows)
+                                           wl.BASE_SEED + 5, args.window, m["pattern"], args.block_rows, m["block_tokens"])
     print(json.dumps(out))
 
 

@@ -70,16 +70,23 @@ typedef struct {
 } burst_rowvec_t;
 
 /*
- * Which (query row, key row) pairs of the step are visible.  A chunk is q_nseg / k_nseg (1 or 2)
- * segments of equal length stored one after the other; local row r lies in segment s = r / seg_len
- * and has global token position  seg_pos[s] + (r - s*seg_len) * pos_stride.
+ * Which (query row, key row) pairs of the step are visible.  A chunk is q_nseg / k_nseg (>= 1)
+ * pieces of equal length stored one after the other; local row r lies in piece s = r / seg_len
+ * and has global token position
+ *     seg_pos[0] + s * (seg_pos[1] - seg_pos[0]) + (r - s*seg_len) * pos_stride
+ * (with one piece seg_pos[1] is not read).  The pieces must follow each other in position order
+ * without overlapping -- seg_pos[1] - seg_pos[0] > (seg_len - 1) * pos_stride -- so that the
+ * position grows with the local row (BURST_ERR_INVALID_ARG otherwise); with more than two pieces a
+ * piece needs at least 32 rows (BURST_ERR_UNSUPPORTED below that).
  *   FULL  : every pair is visible.
  *   CAUSAL: a pair is visible iff position(q) >= position(k)  (Eq. 10: a token attends to itself
  *           and to everything before it); with window > 0 also position(q) - position(k) < window
  *           (sliding-window attention, the sparse pattern of Sec. 3.4: the token itself and the
  *           window - 1 positions before it).  window = 0: no window.  A window needs mode CAUSAL.
- * The zigzag split (Eq. 11-12) is two segments (front piece, back piece); the contiguous split is
- * one; the striped split (Eq. 13-14) is one segment with pos_stride = G.
+ * The zigzag split (Eq. 11-12) is two pieces (front, back); the contiguous split is one; the striped
+ * split (Eq. 13-14) is one piece with pos_stride = G; the block-striped split of block-wise sparse
+ * attention (Sec. 3.4: slice i of every block of N_blk tokens) is N / N_blk pieces of N_blk / G rows,
+ * N_blk positions apart.
  * sq == q_nseg*q_seg_len and sk == k_nseg*k_seg_len must hold.
  * block_mask (device memory, or NULL for none) is a block-wise sparse mask of the step, the other
  * sparse pattern of Sec. 3.4, given on LOCAL rows: byte [q_row / q_block_rows][k_row / k_block_rows]
@@ -172,6 +179,16 @@ int burst_attn_fill_contiguous_mask(int32_t dev_i, int32_t shard_j, int32_t G, i
                                     int32_t causal, burst_mask_t* out);
 int burst_attn_fill_striped_mask(int32_t dev_i, int32_t shard_j, int32_t G, int64_t N,
                                  int32_t causal, burst_mask_t* out);
+/* Block-wise sparse attention (Sec. 3.4, "a strategy similar to striped-way workload balance"): the
+ * sequence is cut into blocks of N_blk tokens (N a multiple of N_blk, N_blk a multiple of G) and device
+ * i holds slice i, N_blk / G consecutive tokens, of every block.  Local row block b of N_blk / G rows is
+ * then global block b on every device, so the step's block_mask is the global M_blk itself
+ * (q_block_rows = k_block_rows = N_blk / G, which the kernels need to be a multiple of 256), and every
+ * step of every device has the same number of visible pairs under a pure block pattern.  The same
+ * holds for the striped split above, which deals token i + G*t of every block to device i and also
+ * stays balanced under the causal rule and a window. */
+int burst_attn_fill_block_striped_mask(int32_t dev_i, int32_t shard_j, int32_t G, int64_t N, int64_t N_blk,
+                                       int32_t causal, burst_mask_t* out);
 
 /* Number of visible (query row, key row) pairs of a step per (batch, head): the benchmark's work
  * unit (4*head_dim flop forward, 10*head_dim backward).  Returns -1 on an invalid mask.  The

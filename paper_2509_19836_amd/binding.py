@@ -64,6 +64,8 @@ for _name in ("zigzag", "contiguous", "striped"):
     _f = getattr(_lib, f"burst_attn_fill_{_name}_mask")
     _f.restype = C.c_int
     _f.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int32, _P(burst_mask_t)]
+_lib.burst_attn_fill_block_striped_mask.restype = C.c_int
+_lib.burst_attn_fill_block_striped_mask.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int32, _P(burst_mask_t)]
 _lib.burst_attn_visible_pairs.restype = C.c_int64
 _lib.burst_attn_visible_pairs.argtypes = [_P(burst_mask_t)]
 _lib.burst_attn_tile_class.restype = C.c_int
@@ -98,6 +100,7 @@ _lib.burst_attn_version.restype = C.c_char_p
 
 EXPORTS = ["burst_attn_step_fwd", "burst_attn_lse_merge", "burst_attn_preprocess_bwd", "burst_attn_step_bwd",
            "burst_attn_fill_zigzag_mask", "burst_attn_fill_contiguous_mask", "burst_attn_fill_striped_mask",
+           "burst_attn_fill_block_striped_mask",
            "burst_attn_visible_pairs", "burst_attn_tile_class", "burst_attn_visible_tile_runs", "burst_attn_mfma_probe", "burst_attn_status_string", "burst_attn_last_hip_error",
            "burst_attn_version", "burst_lm_head_workspace_bytes", "burst_lm_head_loss",
            "burst_lm_head_static_scratch_bytes", "burst_lm_head_loss_noalloc"]
@@ -163,6 +166,12 @@ def burst_attn_fill_contiguous_mask(dev_i, shard_j, G, N, causal=True):
 def burst_attn_fill_striped_mask(dev_i, shard_j, G, N, causal=True):
     m = burst_mask_t()
     _check(_lib.burst_attn_fill_striped_mask(dev_i, shard_j, G, N, int(causal), C.byref(m)))
+    return m
+
+
+def burst_attn_fill_block_striped_mask(dev_i, shard_j, G, N, N_blk, causal=True):
+    m = burst_mask_t()
+    _check(_lib.burst_attn_fill_block_striped_mask(dev_i, shard_j, G, N, N_blk, int(causal), C.byref(m)))
     return m
 
 

@@ -99,6 +99,31 @@ int check_rowvec(const burst_rowvec_t* t, RowvecDev* out) {
   return BURST_OK;
 }
 
+// One axis of a burst_mask_t: nseg pieces of seg_len rows, piece s starting at
+// seg_pos[0] + s * (seg_pos[1] - seg_pos[0]); the pieces must follow each other in position order
+// without overlapping, so that the position grows with the local row.
+int check_axis(int32_t nseg, int64_t seg_len, const int64_t seg_pos[2], int64_t stride, int64_t rows, int32_t* pos0,
+               int32_t* period) {
+  if (nseg < 1 || seg_len < 0) return BURST_ERR_INVALID_ARG;
+  if (seg_len > kMaxRows || nseg > kMaxRows) return BURST_ERR_UNSUPPORTED;
+  if (seg_len * nseg != rows) return BURST_ERR_INVALID_ARG;
+  if (seg_pos[0] < 0) return BURST_ERR_INVALID_ARG;
+  if (seg_pos[0] > kMaxPos) return BURST_ERR_UNSUPPORTED;
+  int64_t per = 0;
+  if (nseg > 1) {
+    per = seg_pos[1] - seg_pos[0];
+    if (seg_pos[1] < 0 || per <= 0) return BURST_ERR_INVALID_ARG;             // pieces in increasing position order
+    if (seg_len > 0 && per <= (seg_len - 1) * stride) return BURST_ERR_INVALID_ARG;   // ... and not overlapping
+    if (per > kMaxPos) return BURST_ERR_UNSUPPORTED;
+    if (nseg > 2 && seg_len < 32) return BURST_ERR_UNSUPPORTED;   // a 32-row register tile may span two pieces, not three
+  }
+  // position just past the last row
+  if (seg_pos[0] + (int64_t)(nseg - 1) * per + seg_len * stride > kMaxPos) return BURST_ERR_UNSUPPORTED;
+  *pos0 = (int32_t)seg_pos[0];
+  *period = (int32_t)per;
+  return BURST_OK;
+}
+
 int check_mask(const burst_mask_t* m, int64_t sq, int64_t sk, MaskDev* out) {
   std::memset(out, 0, sizeof(*out));
   if (!m) {  // no mask given: everything visible
@@ -111,31 +136,19 @@ int check_mask(const burst_mask_t* m, int64_t sq, int64_t sk, MaskDev* out) {
     return BURST_OK;
   }
   if (m->mode != BURST_MASK_FULL && m->mode != BURST_MASK_CAUSAL) return BURST_ERR_INVALID_ARG;
-  if (m->q_nseg < 1 || m->q_nseg > 2 || m->k_nseg < 1 || m->k_nseg > 2) return BURST_ERR_INVALID_ARG;
-  if (m->q_seg_len < 0 || m->k_seg_len < 0 || m->pos_stride < 1) return BURST_ERR_INVALID_ARG;
-  // bounded before it is multiplied below (the products then stay far inside int64)
-  if (m->pos_stride > kMaxPos || m->q_seg_len > kMaxRows || m->k_seg_len > kMaxRows) return BURST_ERR_UNSUPPORTED;
+  if (m->pos_stride < 1) return BURST_ERR_INVALID_ARG;
+  // bounded before it is multiplied (the products then stay far inside int64)
+  if (m->pos_stride > kMaxPos) return BURST_ERR_UNSUPPORTED;
   if (m->window < 0 || (m->window > 0 && m->mode != BURST_MASK_CAUSAL)) return BURST_ERR_INVALID_ARG;
-  if (m->q_seg_len * m->q_nseg != sq || m->k_seg_len * m->k_nseg != sk) return BURST_ERR_INVALID_ARG;
-  for (int s = 0; s < 2; ++s) {
-    if (s < m->q_nseg) {
-      if (m->q_seg_pos[s] < 0) return BURST_ERR_INVALID_ARG;
-      if (m->q_seg_pos[s] + m->q_seg_len * m->pos_stride > kMaxPos) return BURST_ERR_UNSUPPORTED;
-    }
-    if (s < m->k_nseg) {
-      if (m->k_seg_pos[s] < 0) return BURST_ERR_INVALID_ARG;
-      if (m->k_seg_pos[s] + m->k_seg_len * m->pos_stride > kMaxPos) return BURST_ERR_UNSUPPORTED;
-    }
-  }
+  int st = check_axis(m->q_nseg, m->q_seg_len, m->q_seg_pos, m->pos_stride, sq, &out->q_pos0, &out->q_period);
+  if (st != BURST_OK) return st;
+  st = check_axis(m->k_nseg, m->k_seg_len, m->k_seg_pos, m->pos_stride, sk, &out->k_pos0, &out->k_period);
+  if (st != BURST_OK) return st;
   out->causal = (m->mode == BURST_MASK_CAUSAL);
   out->q_nseg = m->q_nseg;
   out->k_nseg = m->k_nseg;
   out->q_seg_len = (int32_t)m->q_seg_len;
   out->k_seg_len = (int32_t)m->k_seg_len;
-  for (int s = 0; s < 2; ++s) {
-    out->q_seg_pos[s] = (int32_t)(s < m->q_nseg ? m->q_seg_pos[s] : 0);
-    out->k_seg_pos[s] = (int32_t)(s < m->k_nseg ? m->k_seg_pos[s] : 0);
-  }
   out->pos_stride = (int32_t)m->pos_stride;
   out->window = (m->window == 0 || m->window >= kNoWindow) ? kNoWindow : (int32_t)m->window;
   if (m->block_mask) {
@@ -378,40 +391,46 @@ int burst_attn_fill_striped_mask(int32_t dev_i, int32_t shard_j, int32_t G, int6
   return BURST_OK;
 }
 
+int burst_attn_fill_block_striped_mask(int32_t dev_i, int32_t shard_j, int32_t G, int64_t N, int64_t N_blk, int32_t causal,
+                                       burst_mask_t* out) {
+  BURST_TRY(fill_common(dev_i, shard_j, G, N, out));
+  if (N_blk < 1 || N % N_blk || N_blk % G) return BURST_ERR_INVALID_ARG;
+  const int64_t m = N_blk / G, pieces = N / N_blk;
+  if (pieces > INT32_MAX) return BURST_ERR_UNSUPPORTED;
+  out->mode = causal ? BURST_MASK_CAUSAL : BURST_MASK_FULL;
+  out->q_nseg = out->k_nseg = (int32_t)pieces;
+  out->q_seg_len = out->k_seg_len = m;
+  out->q_seg_pos[0] = dev_i * m;
+  out->q_seg_pos[1] = dev_i * m + N_blk;
+  out->k_seg_pos[0] = shard_j * m;
+  out->k_seg_pos[1] = shard_j * m + N_blk;
+  out->pos_stride = 1;
+  return BURST_OK;
+}
+
 int64_t burst_attn_visible_pairs(const burst_mask_t* m) {
-  if (!m || m->q_nseg < 1 || m->q_nseg > 2 || m->k_nseg < 1 || m->k_nseg > 2 || m->q_seg_len < 0 ||
-      m->k_seg_len < 0 || m->pos_stride < 1 || m->window < 0 || (m->window > 0 && m->mode != BURST_MASK_CAUSAL))
+  if (!m) return -1;
+  if (m->q_nseg < 1 || m->k_nseg < 1 || m->q_seg_len < 0 || m->k_seg_len < 0 || m->q_seg_len > kMaxRows ||
+      m->k_seg_len > kMaxRows)
     return -1;
-  if (m->mode == BURST_MASK_FULL) return m->q_nseg * m->q_seg_len * m->k_nseg * m->k_seg_len;
-  if (m->mode != BURST_MASK_CAUSAL) return -1;
+  const int64_t sq = m->q_nseg * m->q_seg_len, sk = m->k_nseg * m->k_seg_len;
+  MaskDev mk;
+  if (check_mask(m, sq, sk, &mk) != BURST_OK) return -1;
+  if (!mk.causal) return sq * sk;
+  // per query row: the keys at or before it, minus those that have left its window; positions grow
+  // with the row on both axes, so both sets are prefixes of the key chunk
+  const AxisMap qa = axis_of<true>(mk), ka = axis_of<false>(mk);
   int64_t total = 0;
-  const int64_t s = m->pos_stride;
-  for (int qs = 0; qs < m->q_nseg; ++qs)
-    for (int ks = 0; ks < m->k_nseg; ++ks) {
-      const int64_t a = m->q_seg_pos[qs], b = m->k_seg_pos[ks];
-      for (int64_t i = 0; i < m->q_seg_len; ++i) {
-        // keys j with b + j*s <= a + i*s
-        const int64_t diff = a + i * s - b;
-        if (diff < 0) continue;
-        int64_t cnt = diff / s + 1;                 // keys at or before the query
-        if (cnt > m->k_seg_len) cnt = m->k_seg_len;
-        if (m->window > 0) {                         // minus those that have left its window
-          const int64_t out_of_reach = diff - m->window;   // keys j with b + j*s <= a + i*s - window
-          if (out_of_reach >= 0) {
-            int64_t gone = out_of_reach / s + 1;
-            if (gone > m->k_seg_len) gone = m->k_seg_len;
-            cnt -= gone;
-          }
-        }
-        total += cnt;
-      }
-    }
+  for (int64_t r = 0; r < sq; ++r) {
+    const long long p = axis_position(qa, (int)r);
+    total += rows_lt(ka, p + 1, (int)sk) - rows_lt(ka, p - (long long)mk.window + 1, (int)sk);
+  }
   return total;
 }
 
 // The tile logic of the kernels, run on the host with the code the kernels compile.
 int burst_attn_tile_class(const burst_mask_t* mask, int64_t q0, int64_t q1, int64_t k0, int64_t k1, int32_t method) {
-  if (!mask) return BURST_ERR_INVALID_ARG;
+  if (!mask || mask->q_nseg < 1 || mask->k_nseg < 1) return BURST_ERR_INVALID_ARG;
   const int64_t sq = mask->q_nseg * mask->q_seg_len, sk = mask->k_nseg * mask->k_seg_len;
   MaskDev mk;
   BURST_TRY(check_mask(mask, sq, sk, &mk));
@@ -419,13 +438,13 @@ int burst_attn_tile_class(const burst_mask_t* mask, int64_t q0, int64_t q1, int6
   if (method == 0) return classify(mk, (int)q0, (int)q1, (int)k0, (int)k1, false);
   int lo, hi;
   if (method == 1) {   // query block against a fixed key range
-    range_minmax((int)k0, (int)k1, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride, lo, hi);
+    range_minmax<false>(mk, (int)k0, (int)k1, lo, hi);
     BlockClassifier<true> c;
     c.init(mk, lo, hi, (int)sq, false);
     return c(mk, (int)q0, (int)q1, false);
   }
   if (method == 2) {   // key block against a fixed query range
-    range_minmax((int)q0, (int)q1, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, lo, hi);
+    range_minmax<true>(mk, (int)q0, (int)q1, lo, hi);
     BlockClassifier<false> c;
     c.init(mk, lo, hi, (int)sk, false);
     return c(mk, (int)k0, (int)k1, false);
@@ -435,29 +454,29 @@ int burst_attn_tile_class(const burst_mask_t* mask, int64_t q0, int64_t q1, int6
 
 int burst_attn_visible_tile_runs(const burst_mask_t* mask, int32_t query_axis, int32_t tile_rows, int64_t r0, int64_t r1,
                                  int32_t out_start_len[4]) {
-  if (!mask || !out_start_len) return BURST_ERR_INVALID_ARG;
+  if (!mask || !out_start_len || mask->q_nseg < 1 || mask->k_nseg < 1) return BURST_ERR_INVALID_ARG;
   const int64_t sq = mask->q_nseg * mask->q_seg_len, sk = mask->k_nseg * mask->k_seg_len;
   MaskDev mk;
   BURST_TRY(check_mask(mask, sq, sk, &mk));
   const int64_t other = query_axis ? sk : sq;
   if (r0 < 0 || r1 > other || r0 >= r1) return BURST_ERR_INVALID_ARG;
   int lo, hi;
-  TileRuns tr;
+  TileRun tr;
   if (query_axis) {
-    range_minmax((int)r0, (int)r1, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride, lo, hi);
+    range_minmax<false>(mk, (int)r0, (int)r1, lo, hi);
     if (tile_rows == 64) tr = visible_tiles<true, 64>(mk, lo, hi, (int)sq);
     else if (tile_rows == 256) tr = visible_tiles<true, 256>(mk, lo, hi, (int)sq);
     else return BURST_ERR_UNSUPPORTED;
   } else {
-    range_minmax((int)r0, (int)r1, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, lo, hi);
+    range_minmax<true>(mk, (int)r0, (int)r1, lo, hi);
     if (tile_rows == 64) tr = visible_tiles<false, 64>(mk, lo, hi, (int)sk);
     else if (tile_rows == 128) tr = visible_tiles<false, 128>(mk, lo, hi, (int)sk);
     else return BURST_ERR_UNSUPPORTED;
   }
-  out_start_len[0] = tr.start[0];
-  out_start_len[1] = tr.len[0];
-  out_start_len[2] = tr.start[1];
-  out_start_len[3] = tr.len[1];
+  out_start_len[0] = tr.start;
+  out_start_len[1] = tr.len;
+  out_start_len[2] = 0;   // the kernels' walks are one run; the second pair stays empty
+  out_start_len[3] = 0;
   return BURST_OK;
 }
 

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_bwd_dq_kernel(B
   const int q_w0 = q_blk0 + wave * 32, q_w1 = min(q_w0 + 32, sq);
 
   const int row = min(q_w0 + r, sq - 1);
-  const int qpos = seg_position(row, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride);
+  const int qpos = axis_position(axis_of<true>(mk), row);
   bf16x8 qreg[DK], doreg[DK];
   {
     const __bf16* qs = (const __bf16*)p.q.ptr + b * p.q.sb + hq * p.q.sh + (int64_t)row * p.q.ss + 8 * h;
@@ -79,8 +79,8 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_bwd_dq_kernel(B
 
   // Key tiles the work-group can see, and the class of each against this wave's 32 query rows
   int qlo_blk, qhi_blk, qlo_w = 0, qhi_w = 0;
-  range_minmax(q_blk0, q_blk1, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, qlo_blk, qhi_blk);
-  if (q_w0 < q_w1) range_minmax(q_w0, q_w1, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, qlo_w, qhi_w);
+  range_minmax<true>(mk, q_blk0, q_blk1, qlo_blk, qhi_blk);
+  if (q_w0 < q_w1) range_minmax<true>(mk, q_w0, q_w1, qlo_w, qhi_w);
   BlockClassifier<false> k_class;
   k_class.init(mk, qlo_w, qhi_w, sk, q_w0 >= q_w1);
   auto tile_class = [&](int k0_) { return k_class(mk, k0_, min(k0_ + BK, sk), k0_ + BK > sk); };   // wave-uniform
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_bwd_dq_kernel(B
 #pragma unroll
         for (int v = 0; v < 16; ++v) sd[1][v] = -dval;   // dP - D comes out of the GEMM: the lane owns the row, D is its constant
         gemm_rows_pair<PITCH, DK, kRowsAhead, true>(kt, vt, kb * 32, qreg, doreg, sd[0], sd[1], r, h);   // sd[0] starts from a literal zero
-        if (cls == TILE_PARTIAL) mask_tile<true>(sd[0], mk, k0 + kb * 32 + 4 * h, sk, qpos);
+        if (cls == TILE_PARTIAL) mask_tile<true>(sd[0], mk, k0 + kb * 32, h, sk, qpos);
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           float pr = __builtin_amdgcn_exp2f(c * sd[0][v] - lse2);
@@ -196,7 +196,7 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
   const int k_w0 = k_blk0 + pair * 32, k_w1 = min(k_w0 + 32, sk);
 
   const int krow = min(k_w0 + r, sk - 1);
-  const int kpos = seg_position(krow, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride);
+  const int kpos = axis_position(axis_of<false>(mk), krow);
   bf16x8 xreg[DK];   // K rows (P-wave) or V rows (dS-wave) as the B operand
   {
     const TensorDev& src = ROLE == 0 ? p.k : p.v;
@@ -213,9 +213,9 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
   // Position ranges of the work-group's 128 key rows and of this pair's 32: loop invariants of the
   // tile classification.
   int klo_blk, khi_blk, klo_w = 0, khi_w = 0;
-  range_minmax(k_blk0, k_blk1, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride, klo_blk, khi_blk);
+  range_minmax<false>(mk, k_blk0, k_blk1, klo_blk, khi_blk);
   const bool has_keys = k_w0 < k_w1;
-  if (has_keys) range_minmax(k_w0, k_w1, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride, klo_w, khi_w);
+  if (has_keys) range_minmax<false>(mk, k_w0, k_w1, klo_w, khi_w);
   // Class of a whole query tile against this pair's 32 key rows (same for both waves of the pair).
   // A tile the mask only partly empties is computed whole with the per-element predicate.
   BlockClassifier<true> q_class;
@@ -223,13 +223,12 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
   auto tile_class = [&](int q0) { return q_class(mk, q0, min(q0 + BQ, sq), q0 + BQ > sq); };
 
   // Walk over (query head of the group, query tile that can see the key block), flattened so the
-  // pipeline runs across head boundaries.  The visible tiles of a head are one or two runs of
-  // consecutive tiles; inside a run the cursor moves by adding constants, and only a run or head
-  // change recomputes addresses.
-  const TileRuns qr = visible_tiles<true, BQ>(mk, klo_blk, khi_blk, sq);
-  bool c_valid = qr.total() > 0;                   // the cursor is on an item
-  int c_run = 0, c_left = qr.len[0], c_head = 0;   // cursor: run, tiles left in it, head of the group
-  int q0n = qr.start[0] * BQ;                      // first row of the tile under the cursor
+  // pipeline runs across head boundaries.  The visible tiles of a head are one run of consecutive
+  // tiles; inside it the cursor moves by adding constants, and only a head change recomputes addresses.
+  const TileRun qr = visible_tiles<true, BQ>(mk, klo_blk, khi_blk, sq);
+  bool c_valid = qr.len > 0;                       // the cursor is on an item
+  int c_left = qr.len, c_head = 0;                 // cursor: tiles left in the head's run, head of the group
+  int q0n = qr.start * BQ;                         // first row of the tile under the cursor
 
   TileStager<D, BQ, NT> stage_q, stage_do;         // P-wave only
   float stage_row = 0.f;   // threads [0, BQ): lse of a row; threads [BQ, 2*BQ): D of a row
@@ -240,13 +239,18 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
     stage_q.init(p.q.ss, tid);
     stage_do.init(p.d_o.ss, tid);
   }
+  // which row vector this thread stages (selected once: a select between pointers inside the walk ends up
+  // as an indexed array in scratch memory)
+  const bool stages_lse = tid < BQ;
+  const float* const rowvec_ptr = stages_lse ? p.lse.ptr : p.d.ptr;
+  const int64_t rowvec_sb = stages_lse ? p.lse.sb : p.d.sb, rowvec_sh = stages_lse ? p.lse.sh : p.d.sh;
   auto point = [&]() {   // addresses of the tile under the cursor, from scratch
     if (ROLE != 0) return;
     const int hq = hk * group + c_head;
     q_tile = reinterpret_cast<const char*>((const __bf16*)p.q.ptr + b * p.q.sb + hq * p.q.sh + (int64_t)q0n * p.q.ss);
     do_tile = reinterpret_cast<const char*>((const __bf16*)p.d_o.ptr + b * p.d_o.sb + hq * p.d_o.sh +
                                             (int64_t)q0n * p.d_o.ss);
-    row_head = tid < BQ ? p.lse.ptr + b * p.lse.sb + hq * p.lse.sh : p.d.ptr + b * p.d.sb + hq * p.d.sh;
+    row_head = rowvec_ptr + b * rowvec_sb + hq * rowvec_sh;
   };
   // Open flags of the query tiles against this work-group's key block (block-wise sparse mask)
   const uint8_t* open_flags = nullptr;
@@ -263,14 +267,9 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
       q_tile += q_step;
       do_tile += do_step;
     } else {
-      if (c_run == 0 && qr.len[1] > 0) {
-        c_run = 1;
-      } else {
-        c_run = 0;
-        ++c_head;
-      }
-      c_left = c_run ? qr.len[1] : qr.len[0];
-      q0n = (c_run ? qr.start[1] : qr.start[0]) * BQ;
+      ++c_head;
+      c_left = qr.len;
+      q0n = qr.start * BQ;
       if (c_head < group) point();
       else c_valid = false;
     }
@@ -338,7 +337,7 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
         gemm_rows<PITCH, QBK, DK, kRowsAhead, true>(qt_, 0, xreg, s, r, h);   // first MFMA of each block adds to a literal zero
 #pragma unroll
         for (int qb = 0; qb < QBK; ++qb) {
-          if (cls == TILE_PARTIAL) mask_tile<false>(s[qb], mk, q0 + qb * 32 + 4 * h, sq, kpos);
+          if (cls == TILE_PARTIAL) mask_tile<false>(s[qb], mk, q0 + qb * 32, h, sq, kpos);
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
             const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse2 + qb * 32 + 8 * g + 4 * h);

@@ -40,11 +40,17 @@ constexpr float kLn2 = 0.6931471805599453f;
 enum TileClass : int { TILE_SKIP = 0, TILE_FULL = 1, TILE_PARTIAL = 2 };
 
 // Device copy of the visibility description; positions fit in int32 (checked on the host).
+// Each axis (query rows, key rows) is a chunk of nseg pieces of seg_len rows; piece s starts at position
+// pos0 + s * period and its rows are pos_stride apart.  The pieces are in increasing position order and do
+// not overlap (period > (seg_len - 1) * pos_stride, checked on the host), so the position is a strictly
+// increasing function of the local row: every "rows whose position is below x" set is a prefix of the chunk,
+// and everything the tile logic needs follows from counting such prefixes (rows_lt).
 struct MaskDev {
   int32_t causal;
   int32_t q_nseg, k_nseg;
   int32_t q_seg_len, k_seg_len;
-  int32_t q_seg_pos[2], k_seg_pos[2];
+  int32_t q_pos0, k_pos0;
+  int32_t q_period, k_period;   // 0 with a single piece
   int32_t pos_stride;
   int32_t window;   // causal only: pos(q) - pos(k) < window as well; kNoWindow = unlimited
   // Block-wise sparse mask over local rows (nullptr: none): byte [q_row / blk_q][k_row / blk_k],
@@ -68,17 +74,6 @@ __device__ __forceinline__ void fill_open_flags(const MaskDev& mk, uint8_t* flag
 }
 constexpr int32_t kNoWindow = 0x7fffffff;   // no position difference reaches it (positions < 2^31 - 1)
 
-// Rows r in [0, seg_len) of a segment with r * stride < gap / with r * stride <= room (64-bit: the
-// bounds may carry the window).
-__host__ __device__ __forceinline__ int rows_below(long long gap, int stride, int seg_len) {
-  const long long n = gap <= 0 ? 0 : (gap + stride - 1) / stride;
-  return n < seg_len ? (int)n : seg_len;
-}
-__host__ __device__ __forceinline__ int rows_upto(long long room, int stride, int seg_len) {
-  const long long n = room < 0 ? 0 : room / stride + 1;
-  return n < seg_len ? (int)n : seg_len;
-}
-
 // A [batch, seq, heads, D] tensor; strides in elements.
 struct TensorDev {
   void* ptr;
@@ -90,24 +85,50 @@ struct RowvecDev {
   int64_t sb, sh;
 };
 
-__host__ __device__ __forceinline__ int seg_position(int row, int nseg, int seg_len, const int32_t* seg_pos, int stride) {
-  int s = (nseg > 1 && row >= seg_len) ? 1 : 0;
-  return seg_pos[s] + (row - s * seg_len) * stride;
+// One axis of the mask.
+struct AxisMap {
+  int32_t nseg, seg_len, pos0, period, stride;
+};
+template <bool Q_AXIS>
+__host__ __device__ __forceinline__ AxisMap axis_of(const MaskDev& mk) {
+  return Q_AXIS ? AxisMap{mk.q_nseg, mk.q_seg_len, mk.q_pos0, mk.q_period, mk.pos_stride}
+                : AxisMap{mk.k_nseg, mk.k_seg_len, mk.k_pos0, mk.k_period, mk.pos_stride};
 }
 
-// min / max position over local rows [row0, row1), row1 > row0
-__host__ __device__ __forceinline__ void range_minmax(int row0, int row1, int nseg, int seg_len, const int32_t* seg_pos,
-                                             int stride, int& lo, int& hi) {
-  int last = row1 - 1;
-  if (nseg > 1 && row0 < seg_len && last >= seg_len) {
-    int lo0 = seg_pos[0] + row0 * stride, hi0 = seg_pos[0] + (seg_len - 1) * stride;
-    int lo1 = seg_pos[1], hi1 = seg_pos[1] + (last - seg_len) * stride;
-    lo = lo0 < lo1 ? lo0 : lo1;
-    hi = hi0 > hi1 ? hi0 : hi1;
-  } else {
-    lo = seg_position(row0, nseg, seg_len, seg_pos, stride);
-    hi = seg_position(last, nseg, seg_len, seg_pos, stride);
+// Position of local row `row` (rows past the end of the chunk continue the last piece).
+__host__ __device__ __forceinline__ int axis_position(const AxisMap& ax, int row) {
+  if (ax.nseg <= 1) return ax.pos0 + row * ax.stride;
+  int s = row / ax.seg_len;
+  s = s < ax.nseg - 1 ? s : ax.nseg - 1;
+  return ax.pos0 + s * ax.period + (row - s * ax.seg_len) * ax.stride;
+}
+
+// Number of rows r in [0, rows) whose position is below x (x may carry a window: 64-bit).  The
+// divisions run on values clipped to the chunk's position span, which fits 32 bits.
+__host__ __device__ __forceinline__ int rows_lt(const AxisMap& ax, long long x, int rows) {
+  const long long t = x - ax.pos0;
+  if (t <= 0 || rows <= 0) return 0;
+  const long long span = (long long)(ax.nseg - 1) * ax.period + (long long)(ax.seg_len - 1) * ax.stride;   // position of the last row - pos0
+  if (ax.nseg <= 1) {
+    if (t > (long long)(rows - 1) * ax.stride) return rows;
+    return (int)(((uint32_t)t + (uint32_t)ax.stride - 1u) / (uint32_t)ax.stride);
   }
+  if (t > span) return rows;
+  uint32_t p = ((uint32_t)t - 1u) / (uint32_t)ax.period;          // last piece that starts below x
+  p = p < (uint32_t)(ax.nseg - 1) ? p : (uint32_t)(ax.nseg - 1);
+  const uint32_t rem = (uint32_t)t - p * (uint32_t)ax.period;      // > 0
+  uint32_t n = (rem + (uint32_t)ax.stride - 1u) / (uint32_t)ax.stride;
+  n = n < (uint32_t)ax.seg_len ? n : (uint32_t)ax.seg_len;
+  const int tot = (int)(p * (uint32_t)ax.seg_len + n);
+  return tot < rows ? tot : rows;
+}
+
+// min / max position over local rows [row0, row1), row1 > row0: positions grow with the row
+template <bool Q_AXIS>
+__host__ __device__ __forceinline__ void range_minmax(const MaskDev& mk, int row0, int row1, int& lo, int& hi) {
+  const AxisMap ax = axis_of<Q_AXIS>(mk);
+  lo = axis_position(ax, row0);
+  hi = axis_position(ax, row1 - 1);
 }
 
 // Class of a block whose query positions span [qlo, qhi] and key positions [klo, khi] under a causal
@@ -126,105 +147,86 @@ __host__ __device__ __forceinline__ int classify(const MaskDev& mk, int q0, int 
   if (k1 <= k0 || q1 <= q0) return TILE_SKIP;
   if (!mk.causal) return ragged ? TILE_PARTIAL : TILE_FULL;
   int qlo, qhi, klo, khi;
-  range_minmax(q0, q1, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, qlo, qhi);
-  range_minmax(k0, k1, mk.k_nseg, mk.k_seg_len, mk.k_seg_pos, mk.pos_stride, klo, khi);
+  range_minmax<true>(mk, q0, q1, qlo, qhi);
+  range_minmax<false>(mk, k0, k1, klo, khi);
   return classify_ranges(mk, qlo, qhi, klo, khi, ragged);
 }
 
-// Class of the row block whose positions span [lo, hi] against rows of the other axis spanning
-// [olo, ohi]; Q_ROWS says which side the block is on.  Same decisions as classify(), for callers
-// that keep the other side's range in registers.
-template <bool Q_ROWS>
-__host__ __device__ __forceinline__ int classify_range(const MaskDev& mk, int lo, int hi, int olo, int ohi, bool ragged) {
-  if (!mk.causal) return ragged ? TILE_PARTIAL : TILE_FULL;
-  const int qlo = Q_ROWS ? lo : olo, qhi = Q_ROWS ? hi : ohi, klo = Q_ROWS ? olo : lo, khi = Q_ROWS ? ohi : hi;
-  return classify_ranges(mk, qlo, qhi, klo, khi, ragged);
+// Row intervals of one axis against ONE fixed position range [olo, ohi] of the other axis: the rows
+// that see / are seen by SOME row of the other side are [some_lo, some_hi), those that see / are seen
+// by ALL of them [all_lo, all_hi) (possibly empty).  Positions grow with the row, so each set is one
+// interval of rows, whatever the number of pieces.
+struct RowIntervals {
+  int32_t some_lo, some_hi, all_lo, all_hi;
+};
+template <bool Q_AXIS>
+__host__ __device__ __forceinline__ RowIntervals row_intervals(const MaskDev& mk, int olo, int ohi, int rows, bool other_empty) {
+  RowIntervals iv{0, 0, 0, 0};
+  if (other_empty || rows <= 0) return iv;   // nothing on the other side: every block is empty
+  if (!mk.causal) {
+    iv.some_hi = iv.all_hi = rows;
+    return iv;
+  }
+  const AxisMap ax = axis_of<Q_AXIS>(mk);
+  const long long w = mk.window;
+  if (Q_AXIS) {
+    // query position p sees key position k iff k <= p < k + window; keys span [olo, ohi]
+    iv.some_lo = rows_lt(ax, olo, rows);                    // first p >= olo
+    iv.some_hi = rows_lt(ax, (long long)ohi + w, rows);     // first p >= ohi + window
+    iv.all_lo = rows_lt(ax, ohi, rows);                     // first p >= ohi
+    iv.all_hi = rows_lt(ax, (long long)olo + w, rows);      // first p >= olo + window
+  } else {
+    // key position k is seen from query position p iff p - window < k <= p; queries span [olo, ohi]
+    iv.some_lo = rows_lt(ax, (long long)olo - w + 1, rows);   // first k > olo - window
+    iv.some_hi = rows_lt(ax, (long long)ohi + 1, rows);       // end of k <= ohi
+    iv.all_lo = rows_lt(ax, (long long)ohi - w + 1, rows);    // first k > ohi - window
+    iv.all_hi = rows_lt(ax, (long long)olo + 1, rows);        // end of k <= olo
+  }
+  return iv;
 }
 
-// The same decisions as classify() for many row blocks of one axis against ONE fixed position range
-// [olo, ohi] of the other axis, from per-segment row thresholds computed once: inside a segment
-// positions grow with the row, so on the query axis the rows that see some / all of the keys are a
-// suffix of the segment, on the key axis the rows seen by some / all of the queries a prefix.  A
-// block that straddles the two segments falls back to classify().
+// The same decisions as classify() for many row blocks of one axis against one fixed position range
+// of the other axis, from the row intervals computed once.
 template <bool Q_AXIS>
 struct BlockClassifier {
-  // Per segment, in rows of the chunk: the rows that can see / be seen by SOME row of the other side
-  // are [some_lo, some_hi), those that see / are seen by ALL of them [all_lo, all_hi).  Without a
-  // window one end of each is a segment end.  (Scalar members: the thresholds must stay in registers.)
-  int32_t some_lo0, some_hi0, all_lo0, all_hi0, some_lo1, some_hi1, all_lo1, all_hi1;
-  int32_t olo, ohi, seg_len, two, empty;
+  RowIntervals iv;   // (scalar members: the thresholds must stay in registers)
 
-  __host__ __device__ __forceinline__ void init(const MaskDev& mk, int olo_, int ohi_, int rows, bool other_empty) {
-    olo = olo_;
-    ohi = ohi_;
-    empty = other_empty;
-    two = (Q_AXIS ? mk.q_nseg : mk.k_nseg) > 1;
-    seg_len = two ? (Q_AXIS ? mk.q_seg_len : mk.k_seg_len) : rows;
-    segment(mk, 0, Q_AXIS ? mk.q_seg_pos[0] : mk.k_seg_pos[0], some_lo0, some_hi0, all_lo0, all_hi0);
-    segment(mk, seg_len, Q_AXIS ? mk.q_seg_pos[1] : mk.k_seg_pos[1], some_lo1, some_hi1, all_lo1, all_hi1);
-  }
-  __host__ __device__ __forceinline__ void segment(const MaskDev& mk, int start, int pos0, int32_t& some_lo,
-                                                   int32_t& some_hi, int32_t& all_lo, int32_t& all_hi) const {
-    const int st = mk.pos_stride;
-    const long long w = mk.window;
-    if (empty) {   // nothing on the other side: every block is empty
-      some_lo = some_hi = all_lo = all_hi = start;
-    } else if (!mk.causal) {
-      some_lo = all_lo = start;
-      some_hi = all_hi = start + seg_len;
-    } else if (Q_AXIS) {
-      // query position p sees key position k iff k <= p < k + window; keys span [olo, ohi]
-      some_lo = start + rows_below((long long)olo - pos0, st, seg_len);        // first p >= olo
-      some_hi = start + rows_below((long long)ohi + w - pos0, st, seg_len);    // first p >= ohi + window
-      all_lo = start + rows_below((long long)ohi - pos0, st, seg_len);         // first p >= ohi
-      all_hi = start + rows_below((long long)olo + w - pos0, st, seg_len);     // first p >= olo + window
-    } else {
-      // key position k is seen from query position p iff p - window < k <= p; queries span [olo, ohi]
-      some_lo = start + rows_below((long long)olo - w + 1 - pos0, st, seg_len);   // first k > olo - window
-      some_hi = start + rows_upto((long long)ohi - pos0, st, seg_len);            // end of k <= ohi
-      all_lo = start + rows_below((long long)ohi - w + 1 - pos0, st, seg_len);    // first k > ohi - window
-      all_hi = start + rows_upto((long long)olo - pos0, st, seg_len);             // end of k <= olo
-    }
+  __host__ __device__ __forceinline__ void init(const MaskDev& mk, int olo, int ohi, int rows, bool other_empty) {
+    iv = row_intervals<Q_AXIS>(mk, olo, ohi, rows, other_empty);
   }
   // block of rows [r0, r1), r1 > r0, both inside the chunk
-  __host__ __device__ __forceinline__ int operator()(const MaskDev& mk, int r0, int r1, bool ragged) const {
+  __host__ __device__ __forceinline__ int operator()(const MaskDev&, int r0, int r1, bool ragged) const {
     // bitwise logic and selects only: this runs once per tile in every wave, and short-circuit
     // operators compile to a chain of scalar branches
-    if ((two != 0) & (r0 < seg_len) & (r1 > seg_len)) return classify_straddle(mk, r0, r1, ragged);   // rare
-    const bool second = (two != 0) & (r0 >= seg_len);
-    const int s_lo = second ? some_lo1 : some_lo0, s_hi = second ? some_hi1 : some_hi0;
-    const int a_lo = second ? all_lo1 : all_lo0, a_hi = second ? all_hi1 : all_hi0;
-    const bool skip = (r1 <= s_lo) | (r0 >= s_hi);
-    const bool full = (r0 >= a_lo) & (r1 <= a_hi) & !ragged;
+    const bool skip = (r1 <= iv.some_lo) | (r0 >= iv.some_hi);
+    const bool full = (r0 >= iv.all_lo) & (r1 <= iv.all_hi) & !ragged;
     const int cls = full ? TILE_FULL : TILE_PARTIAL;
     return skip ? TILE_SKIP : cls;
-  }
-  __host__ __device__ __forceinline__ int classify_straddle(const MaskDev& mk, int r0, int r1, bool ragged) const {
-    if (empty) return TILE_SKIP;
-    const int p0 = Q_AXIS ? mk.q_seg_pos[0] : mk.k_seg_pos[0], p1 = Q_AXIS ? mk.q_seg_pos[1] : mk.k_seg_pos[1];
-    const int lo0 = p0 + r0 * mk.pos_stride, hi0 = p0 + (seg_len - 1) * mk.pos_stride;
-    const int lo1 = p1, hi1 = p1 + (r1 - 1 - seg_len) * mk.pos_stride;
-    return classify_range<Q_AXIS>(mk, lo0 < lo1 ? lo0 : lo1, hi0 > hi1 ? hi0 : hi1, olo, ohi, ragged);
   }
 };
 
 // Per-element mask of one 32x32 accumulator tile whose 16 registers of a lane run over rows
-// row0 + 8*(v/4) + (v%4)  (row0 already includes the lane's 4*h) of the OTHER side than the lane's
-// own row: KEYS_IN_REGS = true, registers are key rows and the lane owns a query (position
+// base_row + 4*h + 8*(v/4) + (v%4) of the OTHER side than the lane's own row (base_row: first of the 32
+// rows, wave-uniform): KEYS_IN_REGS = true, registers are key rows and the lane owns a query (position
 // lane_pos); false, registers are query rows and the lane owns a key.  Invisible entries and rows
-// >= n_rows become -inf.  Written with selects only, no divergent control flow.
+// >= n_rows become -inf.  The 32 rows lie in at most two consecutive pieces (a piece has at least 32
+// rows whenever there are more than two, checked on the host).  Written with selects only, no
+// divergent control flow.
 template <bool KEYS_IN_REGS>
-__device__ __forceinline__ void mask_tile(f32x16& s, const MaskDev& mk, int row0, int n_rows, int lane_pos) {
-  const int nseg = KEYS_IN_REGS ? mk.k_nseg : mk.q_nseg;
-  const int seg_len = KEYS_IN_REGS ? mk.k_seg_len : mk.q_seg_len;
-  const int pos0 = KEYS_IN_REGS ? mk.k_seg_pos[0] : mk.q_seg_pos[0];
-  const int pos1 = KEYS_IN_REGS ? mk.k_seg_pos[1] : mk.q_seg_pos[1];
-  const int split = nseg > 1 ? seg_len : 0x7fffffff;
+__device__ __forceinline__ void mask_tile(f32x16& s, const MaskDev& mk, int base_row, int h, int n_rows, int lane_pos) {
+  const AxisMap ax = axis_of<!KEYS_IN_REGS>(mk);
+  int split = 0x7fffffff, pos_a = ax.pos0, pos_b = ax.pos0;   // position = pos_a (rows < split) or pos_b, + row * stride
+  if (ax.nseg > 1) {
+    int s0 = base_row / ax.seg_len;
+    s0 = s0 < ax.nseg - 1 ? s0 : ax.nseg - 1;
+    pos_a = ax.pos0 + s0 * (ax.period - ax.seg_len * ax.stride);
+    pos_b = pos_a + ax.period - ax.seg_len * ax.stride;
+    split = s0 < ax.nseg - 1 ? (s0 + 1) * ax.seg_len : 0x7fffffff;
+  }
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
-    const int row = row0 + 8 * (v >> 2) + (v & 3);
-    const bool second = row >= split;
-    const int pos = (second ? pos1 : pos0) + (row - (second ? seg_len : 0)) * mk.pos_stride;
+    const int row = base_row + 4 * h + 8 * (v >> 2) + (v & 3);
+    const int pos = (row >= split ? pos_b : pos_a) + row * ax.stride;
     const int diff = KEYS_IN_REGS ? lane_pos - pos : pos - lane_pos;   // pos(q) - pos(k)
     const bool ordered = (diff >= 0) & (diff < mk.window);
     const bool vis = (row < n_rows) & ((mk.causal == 0) | ordered);
@@ -284,9 +286,9 @@ __device__ __forceinline__ float half_swap(float x) {
   return __shfl_xor(x, 32, 64);
 }
 
-// The tiles of an axis that have any visible pair, as up to two runs of consecutive tile indices
-// (a causal mask over one- or two-segment chunks never needs more).  Only these are launched: an
-// empty work-group costs a dispatch slot, and many of them in a row starve the other CUs.
+// The tiles of an axis that have any visible pair against the WHOLE other chunk, as up to two runs of
+// consecutive tile indices (found by the host; with more runs every tile is launched).  Only these are
+// launched: an empty work-group costs a dispatch slot, and many of them in a row starve the other CUs.
 struct TileRuns {
   int32_t start[2], len[2];
   __host__ __device__ int total() const { return len[0] + len[1]; }
@@ -294,51 +296,18 @@ struct TileRuns {
 };
 
 // Tiles of TILE rows along the query axis (Q_AXIS) or the key axis that can hold a pair visible to
-// the other side, whose positions span [olo, ohi], in closed form: under a causal mask the rows of a
-// query segment that see some key are those with olo <= position < ohi + window, the rows of a key
-// segment seen by some query those with olo - window < position <= ohi: one stretch of rows per
-// segment, and a chunk has at most two segments, hence at most two runs.  A tile in a run may still
-// turn out empty for a narrower row range; a tile outside the runs never holds a visible pair.
+// the other side, whose positions span [olo, ohi]: the rows that see / are seen by some row of the other
+// side are one interval of rows (row_intervals), hence one run of consecutive tiles.  A tile in the run
+// may still turn out empty for a narrower row range; a tile outside it never holds a visible pair.
+struct TileRun {
+  int32_t start, len;
+};
 template <bool Q_AXIS, int TILE>
-__host__ __device__ __forceinline__ TileRuns visible_tiles(const MaskDev& mk, int olo, int ohi, int rows) {
-  TileRuns tr{{0, 0}, {0, 0}};
-  if (rows <= 0) return tr;
-  if (!mk.causal) {
-    tr.len[0] = (rows + TILE - 1) / TILE;
-    return tr;
-  }
-  const int nseg = Q_AXIS ? mk.q_nseg : mk.k_nseg;
-  const int seg_len = nseg > 1 ? (Q_AXIS ? mk.q_seg_len : mk.k_seg_len) : rows;
-  const long long w = mk.window;
-  int n = 0, prev_end = 0;
-#pragma unroll
-  for (int s = 0; s < 2; ++s) {   // constant indices only: the mask must stay in registers
-    if (s >= nseg) break;
-    const int pos0 = Q_AXIS ? mk.q_seg_pos[s] : mk.k_seg_pos[s];
-    // visible rows of the segment, counted from its start
-    const int r0 = Q_AXIS ? rows_below((long long)olo - pos0, mk.pos_stride, seg_len)
-                          : rows_below((long long)olo - w + 1 - pos0, mk.pos_stride, seg_len);
-    const int r1 = Q_AXIS ? rows_below((long long)ohi + w - pos0, mk.pos_stride, seg_len)
-                          : rows_upto((long long)ohi - pos0, mk.pos_stride, seg_len);
-    if (r0 >= r1) continue;
-    int a = (s * seg_len + r0) / TILE;
-    const int b = (s * seg_len + r1 + TILE - 1) / TILE;
-    a = a > prev_end ? a : prev_end;
-    if (a >= b) continue;
-    if (s == 1 && n == 1 && a == prev_end) {
-      tr.len[0] += b - a;
-    } else if (n == 0) {
-      tr.start[0] = a;
-      tr.len[0] = b - a;
-      n = 1;
-    } else {
-      tr.start[1] = a;
-      tr.len[1] = b - a;
-      n = 2;
-    }
-    prev_end = b;
-  }
-  return tr;
+__host__ __device__ __forceinline__ TileRun visible_tiles(const MaskDev& mk, int olo, int ohi, int rows) {
+  const RowIntervals iv = row_intervals<Q_AXIS>(mk, olo, ohi, rows, false);
+  if (iv.some_lo >= iv.some_hi) return TileRun{0, 0};
+  const int first = iv.some_lo / TILE;
+  return TileRun{first, (iv.some_hi + TILE - 1) / TILE - first};
 }
 
 // Stage a [ROWS x D] bf16 tile: global (row-major, row stride `ss` elements) -> registers -> LDS,
@@ -399,14 +368,12 @@ struct TileStager {
 };
 
 // Walk of a query block over the key tiles (BK rows of K and of V) it can see, with the staging
-// of the tiles.  The visible tiles form at most two runs of consecutive tiles; inside a run the
-// next tile is the next BK rows, so the cursor and the two tile addresses move by adding constants
-// and a load needs no address arithmetic; only the jump to the second run multiplies.
+// of the tiles.  The visible tiles are one run of consecutive tiles, so the cursor and the two tile
+// addresses move by adding constants and a load needs no address arithmetic.
 template <int D, int BK, int NT>
 struct KvWalk {
   TileStager<D, BK, NT> stage_k, stage_v;
-  TileRuns runs;
-  int run, left, k0;      // cursor: run, tiles left in it (0: the walk is over), first key row of its tile
+  int left, k0;           // cursor: tiles left in the run (0: the walk is over), first key row of its tile
   int sk;
   const uint8_t* open;    // LDS flags per key tile from a block-wise sparse mask, or nullptr
   const char *k_base, *v_base, *k_tile, *v_tile;   // row 0 of the head; first row of the cursor's tile
@@ -418,10 +385,9 @@ struct KvWalk {
                                        int q_lo, int q_hi, int tid, const uint8_t* open_flags) {
     sk = sk_;
     open = open_flags;
-    runs = visible_tiles<false, BK>(mk, q_lo, q_hi, sk);
-    run = 0;
-    left = runs.len[0];
-    k0 = runs.start[0] * BK;
+    const TileRun run = visible_tiles<false, BK>(mk, q_lo, q_hi, sk);
+    left = run.len;
+    k0 = run.start * BK;
     k_row = k.ss * 2;
     v_row = v.ss * 2;
     k_base = reinterpret_cast<const char*>((const __bf16*)k.ptr + b * k.sb + hk * k.sh);
@@ -443,17 +409,10 @@ struct KvWalk {
     }
   }
   __device__ __forceinline__ void step() {
-    if (--left > 0) {
-      k0 += BK;
-      k_tile += BK * k_row;
-      v_tile += BK * v_row;
-    } else if (run == 0) {
-      run = 1;
-      left = runs.len[1];
-      k0 = runs.start[1] * BK;
-      k_tile = k_base + k0 * k_row;
-      v_tile = v_base + k0 * v_row;
-    }
+    --left;
+    k0 += BK;
+    k_tile += BK * k_row;
+    v_tile += BK * v_row;
   }
   // skip tiles that the block mask closes
   __device__ __forceinline__ void seek() {

@@ -43,7 +43,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
   // Q as the B operand of S^T = K Q^T: lane holds Q[row][16*ks + 8h .. +7]
   bf16x8 qreg[DK];
   const int row = min(q_w0 + r, sq - 1);
-  const int qpos = seg_position(row, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride);
+  const int qpos = axis_position(axis_of<true>(mk), row);
   {
     const __bf16* src = (const __bf16*)p.q.ptr + b * p.q.sb + hq * p.q.sh + (int64_t)row * p.q.ss + 8 * h;
 #pragma unroll
@@ -60,8 +60,8 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
 
   // Key tiles the work-group can see, and the class of each against this wave's 32 query rows
   int qlo_blk, qhi_blk, qlo_w = 0, qhi_w = 0;
-  range_minmax(q_blk0, q_blk1, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, qlo_blk, qhi_blk);
-  if (q_w0 < q_w1) range_minmax(q_w0, q_w1, mk.q_nseg, mk.q_seg_len, mk.q_seg_pos, mk.pos_stride, qlo_w, qhi_w);
+  range_minmax<true>(mk, q_blk0, q_blk1, qlo_blk, qhi_blk);
+  if (q_w0 < q_w1) range_minmax<true>(mk, q_w0, q_w1, qlo_w, qhi_w);
   BlockClassifier<false> k_class;
   k_class.init(mk, qlo_w, qhi_w, sk, q_w0 >= q_w1);
   auto tile_class = [&](int k0_) { return k_class(mk, k0_, min(k0_ + BK, sk), k0_ + BK > sk); };   // wave-uniform
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
       __builtin_amdgcn_sched_barrier(0);
       if (cls == TILE_PARTIAL) {
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) mask_tile<true>(s[kb], mk, k0 + kb * 32 + 4 * h, sk, qpos);
+        for (int kb = 0; kb < KB; ++kb) mask_tile<true>(s[kb], mk, k0 + kb * 32, h, sk, qpos);
       }
       float mx = s[0][0];
 #pragma unroll

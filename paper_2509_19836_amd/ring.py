@@ -13,9 +13,10 @@ def ring_order(i, G):
     return [(i - t) % G for t in range(G)]
 
 
-def fill_mask(kind, i, j, G, N, window=0):
-    """kind: "full" / "causal" (contiguous split), "zigzag", "striped"; window > 0: sliding-window
-    attention over the causal kinds (each token sees itself and the window - 1 positions before it)."""
+def fill_mask(kind, i, j, G, N, window=0, N_blk=0):
+    """kind: "full" / "causal" (contiguous split), "zigzag", "striped", "block_striped" (slice i of every
+    block of N_blk tokens); window > 0: sliding-window attention over the causal kinds (each token sees
+    itself and the window - 1 positions before it)."""
     if kind == "full":
         m = lib.burst_attn_fill_contiguous_mask(i, j, G, N, False)
     elif kind == "causal":
@@ -24,6 +25,8 @@ def fill_mask(kind, i, j, G, N, window=0):
         m = lib.burst_attn_fill_zigzag_mask(i, j, G, N, True)
     elif kind == "striped":
         m = lib.burst_attn_fill_striped_mask(i, j, G, N, True)
+    elif kind == "block_striped":
+        m = lib.burst_attn_fill_block_striped_mask(i, j, G, N, N_blk, True)
     else:
         raise ValueError(kind)
     m.window = window
@@ -35,21 +38,23 @@ def mask_positions(mask, side):
     import numpy as np
     nseg, seg_len, seg_pos = ((mask.q_nseg, mask.q_seg_len, mask.q_seg_pos) if side == "q" else
                               (mask.k_nseg, mask.k_seg_len, mask.k_seg_pos))
-    return np.concatenate([seg_pos[s] + np.arange(seg_len, dtype=np.int64) * mask.pos_stride for s in range(nseg)])
+    period = seg_pos[1] - seg_pos[0] if nseg > 1 else 0
+    return np.concatenate([seg_pos[0] + s * period + np.arange(seg_len, dtype=np.int64) * mask.pos_stride
+                           for s in range(nseg)])
 
 
-def ring_forward(i, G, N, kind, scale, q_i, k_shards, v_shards, o_acc, lse_acc, stream=None, window=0):
+def ring_forward(i, G, N, kind, scale, q_i, k_shards, v_shards, o_acc, lse_acc, stream=None, window=0, N_blk=0):
     """o_acc / lse_acc must hold (0, -inf) on entry; they hold (O_i, Lse_i) on return."""
     B, n, Hq, d = q_i.shape
     for j in ring_order(i, G):
         k_j, v_j = k_shards[j], v_shards[j]
         shp = lib.shape(B, Hq, k_j.shape[2], d, n, k_j.shape[1], scale)
-        lib.burst_attn_step_fwd(shp, fill_mask(kind, i, j, G, N, window), q_i, k_j, v_j,
+        lib.burst_attn_step_fwd(shp, fill_mask(kind, i, j, G, N, window, N_blk), q_i, k_j, v_j,
                                 o_acc=o_acc, lse_acc=lse_acc, stream=stream)
 
 
 def ring_backward(i, G, N, kind, scale, q_i, do_i, o_i, lse_i, d_i, k_shards, v_shards, dq_i, dk_shards,
-                  dv_shards, stream=None, window=0):
+                  dv_shards, stream=None, window=0, N_blk=0):
     """D_i once, then one backward step per shard; dq_i, dk_shards[j], dv_shards[j] are fp32
     accumulators ("+=")."""
     B, n, Hq, d = q_i.shape
@@ -59,6 +64,6 @@ def ring_backward(i, G, N, kind, scale, q_i, do_i, o_i, lse_i, d_i, k_shards, v_
     for j in ring_order(i, G):
         k_j, v_j = k_shards[j], v_shards[j]
         shp = lib.shape(B, Hq, k_j.shape[2], d, n, k_j.shape[1], scale)
-        lib.burst_attn_step_bwd(shp, fill_mask(kind, i, j, G, N, window), q_i, k_j, v_j, do_i, lse_i, d_i,
+        lib.burst_attn_step_bwd(shp, fill_mask(kind, i, j, G, N, window, N_blk), q_i, k_j, v_j, do_i, lse_i, d_i,
                                 dq=dq_i, dk=dk_shards[j], dv=dv_shards[j], accumulate_flags=flags,
                                 stream=stream)

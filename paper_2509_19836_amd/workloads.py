@@ -111,18 +111,24 @@ def block_sparse_pattern(n_blocks, density, seed):
     return pat
 
 
-def local_block_mask(pattern, pos_q, pos_k, block_rows):
-    """The slice of a global block pattern that a ring step sees, on LOCAL row blocks: entry
-    [a][b] is the pattern entry of the global blocks holding local rows a*block_rows and
-    b*block_rows.  pos_q / pos_k: global positions of the local rows; every local block must lie
-    inside one global block (true for the contiguous and zigzag splits when block_rows divides the
-    piece length)."""
+def local_block_mask(pattern, pos_q, pos_k, block_rows, global_block=None):
+    """The slice of a global block pattern that a ring step sees, on LOCAL row blocks of block_rows
+    rows: entry [a][b] is the pattern entry of the global blocks (of global_block tokens; default
+    block_rows) that hold local row blocks a and b.  pos_q / pos_k: global positions of the local rows;
+    every local block must lie inside one global block.  That holds for the contiguous and zigzag splits
+    when block_rows = global_block divides the piece length, and for the two balanced splits of
+    block-wise sparse attention (slice i or stripe i of every block) with block_rows = global_block / G."""
+    global_block = global_block or block_rows
     pos_q, pos_k = np.asarray(pos_q), np.asarray(pos_k)
+    blocks = []
     for pos in (pos_q, pos_k):
-        first, last = pos[::block_rows] // block_rows, pos[block_rows - 1::block_rows] // block_rows
-        if pos.size % block_rows or not np.array_equal(first, last):
+        if pos.size % block_rows:
+            raise ValueError("the chunk is not a whole number of local row blocks")
+        g = (pos // global_block).reshape(-1, block_rows)
+        if not (g == g[:, :1]).all():
             raise ValueError("local row blocks straddle global blocks")
-    return np.ascontiguousarray(pattern[np.ix_(pos_q[::block_rows] // block_rows, pos_k[::block_rows] // block_rows)])
+        blocks.append(g[:, 0])
+    return np.ascontiguousarray(pattern[np.ix_(blocks[0], blocks[1])])
 
 
 def lm_head_tensors(seed, n_tokens, d_model, vocab, ignored=0):

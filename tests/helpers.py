@@ -14,12 +14,13 @@ def mask_positions(mask, side):
     nseg = mask.q_nseg if side == "q" else mask.k_nseg
     seg_len = mask.q_seg_len if side == "q" else mask.k_seg_len
     seg_pos = mask.q_seg_pos if side == "q" else mask.k_seg_pos
-    return np.concatenate([seg_pos[s] + np.arange(seg_len, dtype=np.int64) * mask.pos_stride
+    period = seg_pos[1] - seg_pos[0] if nseg > 1 else 0
+    return np.concatenate([seg_pos[0] + s * period + np.arange(seg_len, dtype=np.int64) * mask.pos_stride
                            for s in range(nseg)])
 
 
-def fill_mask(lib, kind, i, j, G, N, window=0):
-    """kind: full | causal (contiguous split) | zigzag | striped; window > 0 adds a sliding window."""
+def fill_mask(lib, kind, i, j, G, N, window=0, N_blk=0):
+    """kind: full | causal (contiguous split) | zigzag | striped | block_striped; window > 0 adds a sliding window."""
     if kind == "full":
         m = lib.burst_attn_fill_contiguous_mask(i, j, G, N, False)
     elif kind == "causal":
@@ -28,13 +29,17 @@ def fill_mask(lib, kind, i, j, G, N, window=0):
         m = lib.burst_attn_fill_zigzag_mask(i, j, G, N, True)
     elif kind == "striped":
         m = lib.burst_attn_fill_striped_mask(i, j, G, N, True)
+    elif kind == "block_striped":
+        m = lib.burst_attn_fill_block_striped_mask(i, j, G, N, N_blk, True)
     else:
         raise ValueError(kind)
     m.window = window
     return m
 
 
-def oracle_positions(oc, kind, i, G, N):
+def oracle_positions(oc, kind, i, G, N, N_blk=0):
+    if kind == "block_striped":
+        return oc.block_striped_positions(i, G, N, N_blk)
     if kind in ("full", "causal"):
         return oc.contiguous_positions(i, G, N)
     if kind == "zigzag":

@@ -237,10 +237,12 @@ def test_workload_generators_are_seeded_and_exact():
     assert stds.min() > 0.4 and stds.max() < 2.2 and stds.std() > 0.05
 
 
-def _custom_mask(lib, q_pos, k_pos, q_len, k_len, stride, causal=True):
+def _custom_mask(lib, q_pos, k_pos, q_len, k_len, stride, causal=True, q_nseg=None, k_nseg=None):
+    """q_pos / k_pos: start of the first piece, or of the first two (their distance is the period of
+    q_nseg / k_nseg pieces)."""
     m = lib.burst_mask_t()
     m.mode = lib.BURST_MASK_CAUSAL if causal else lib.BURST_MASK_FULL
-    m.q_nseg, m.k_nseg = len(q_pos), len(k_pos)
+    m.q_nseg, m.k_nseg = q_nseg or len(q_pos), k_nseg or len(k_pos)
     for s, p in enumerate(q_pos):
         m.q_seg_pos[s] = p
     for s, p in enumerate(k_pos):
@@ -262,7 +264,14 @@ def _tile_logic_masks(lib):
             for j in range(G):
                 out.append(lib.burst_attn_fill_contiguous_mask(i, j, G, N))
                 out.append(lib.burst_attn_fill_striped_mask(i, j, G, N))
-    out.append(_custom_mask(lib, (700, 10), (300, 0), 150, 170, 1))     # second segment earlier than the first
+    out.append(_custom_mask(lib, (10, 700), (0, 300), 150, 170, 1))     # pieces of different lengths on the two axes
+    # many pieces (the block-striped split of block-wise sparse attention), also with piece lengths that are
+    # not multiples of the tile sizes, a position stride inside the pieces, different piece counts per axis
+    for G, N, N_blk in ((2, 1024, 256), (4, 1536, 384)):
+        for i, j in ((0, 0), (1, 0), (0, G - 1), (G - 1, 1)):
+            out.append(lib.burst_attn_fill_block_striped_mask(i, j, G, N, N_blk))
+    out.append(_custom_mask(lib, (7, 307), (0, 450), 100, 150, 2, q_nseg=5, k_nseg=3))
+    out.append(_custom_mask(lib, (0, 100), (50,), 40, 700, 1, q_nseg=9))
     out.append(_custom_mask(lib, (5, 900), (0,), 130, 400, 3))          # stride 3, mixed segment counts
     out.append(_custom_mask(lib, (40,), (0, 1000), 333, 200, 2))
     out.append(_custom_mask(lib, (0, 512), (0, 512), 256, 256, 1, causal=False))
@@ -270,7 +279,10 @@ def _tile_logic_masks(lib):
         for m0 in (lib.burst_attn_fill_zigzag_mask(1, 0, 2, 2 * 2 * 160), lib.burst_attn_fill_zigzag_mask(0, 1, 2, 2 * 2 * 160),
                    lib.burst_attn_fill_zigzag_mask(2, 2, 4, 4 * 2 * 96), lib.burst_attn_fill_contiguous_mask(1, 0, 2, 600),
                    lib.burst_attn_fill_contiguous_mask(1, 1, 2, 600), lib.burst_attn_fill_striped_mask(3, 1, 4, 1024),
-                   lib.burst_attn_fill_striped_mask(0, 2, 4, 1024), _custom_mask(lib, (5, 900), (0,), 130, 400, 3)):
+                   lib.burst_attn_fill_striped_mask(0, 2, 4, 1024), _custom_mask(lib, (5, 900), (0,), 130, 400, 3),
+                   lib.burst_attn_fill_block_striped_mask(1, 0, 2, 1024, 256), lib.burst_attn_fill_block_striped_mask(0, 1, 2, 1024, 256),
+                   lib.burst_attn_fill_block_striped_mask(3, 3, 4, 1536, 384),
+                   _custom_mask(lib, (7, 307), (0, 450), 100, 150, 2, q_nseg=5, k_nseg=3)):
             m0.window = window
             out.append(m0)
     return out
@@ -330,9 +342,32 @@ def test_visible_tile_runs_match_brute_force(lib):
                 else:   # with a window the runs may hold tiles that turn out empty, never miss one
                     assert all(g or not w for g, w in zip(got, want)), (query_axis, tile, r0, r1, runs)
                     o_nseg, o_len = (m.k_nseg, m.k_seg_len) if query_axis else (m.q_nseg, m.q_seg_len)
-                    if not (o_nseg == 2 and r0 < o_len < r1) and m.window >= m.pos_stride:
+                    w_nseg = m.q_nseg if query_axis else m.k_nseg
+                    if o_nseg <= 2 and w_nseg <= 2 and not (o_nseg == 2 and r0 < o_len < r1) and m.window >= m.pos_stride:
                         # other rows inside one segment: only the tiles at the ends of a run can be empty
                         assert sum(got) <= sum(want) + 4, (query_axis, tile, r0, r1, runs, sum(want))
+
+
+def test_pieces_must_be_in_position_order_and_not_overlap(lib):
+    """The tile logic counts prefixes of rows below a position, which needs positions that grow with
+    the local row: pieces out of order or overlapping are refused, and so are more than two pieces of
+    fewer than 32 rows (a 32-row register tile may span two pieces, not three)."""
+    INV, UNS = lib.BURST_ERR_INVALID_ARG, lib.BURST_ERR_UNSUPPORTED
+    raw = lib.raw()
+    cls = lambda m: raw.burst_attn_tile_class(C.byref(m), 0, 1, 0, 1, 0)
+    assert cls(_custom_mask(lib, (700, 10), (0, 300), 150, 170, 1)) == INV          # second piece before the first
+    assert cls(_custom_mask(lib, (0, 100), (0, 300), 150, 170, 1)) == INV           # pieces overlap
+    assert cls(_custom_mask(lib, (0, 298), (0, 400), 150, 170, 2)) == INV           # ... because of the stride
+    assert cls(_custom_mask(lib, (0, 299), (0, 400), 150, 170, 2)) >= 0
+    assert cls(_custom_mask(lib, (0, 64), (0,), 16, 64, 1, q_nseg=3)) == UNS         # three pieces of 16 rows
+    assert cls(_custom_mask(lib, (0, 64), (0,), 16, 64, 1, q_nseg=2)) >= 0
+    assert cls(_custom_mask(lib, (0, 1 << 30), (0,), 64, 64, 1, q_nseg=4)) == UNS    # positions beyond 2^31
+    assert lib.burst_attn_visible_pairs(_custom_mask(lib, (700, 10), (0, 300), 150, 170, 1)) == -1
+    # the helper: N_blk must divide N and be a multiple of G
+    m = lib.burst_mask_t()
+    for args in ((0, 0, 4, 1024, 100), (0, 0, 4, 1024, 258), (0, 0, 4, 1024, 0), (4, 0, 4, 1024, 256)):
+        assert raw.burst_attn_fill_block_striped_mask(*args, 1, C.byref(m)) == INV
+    assert raw.burst_attn_fill_block_striped_mask(1, 2, 4, 1024, 256, 1, None) == INV
 
 
 def test_tile_logic_rejects_bad_arguments(lib):
