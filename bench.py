@@ -27,7 +27,8 @@ PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flo
 # below).  Counters cannot be read from inside the process, so the figure is the profiled one: it is
 # reported with the profile it came from and its date, and only for the workload that was profiled.
 PROFILED_TRAFFIC = {
-    2: {"bytes": 1.922e9, "profile": "profiles/bench_config2_pmc_hbm_traffic.md", "taken": "round-1 kernels"},
+    2: {"bytes": 1.922e9, "profile": "profiles/bench_config2_pmc_hbm_traffic.md", "taken": "2026-11-27, same dK/dV kernel"},
+    5: {"bytes": 3.387e11, "profile": "profiles/bench_config5_pmc_hbm_traffic.md", "taken": "2026-11-28, same dK/dV kernel"},
 }
 # --lm-head, default shape: bytes per call over all its launches (profiles/bench_lm_head_kernel_trace_and_counters.md)
 PROFILED_LM_HEAD_TRAFFIC_BYTES = 2.73e10
