@@ -21,6 +21,10 @@
 
 namespace burst {
 
+#ifndef BURST_FOLD_SCALE
+#define BURST_FOLD_SCALE 1   // dK/dV kernel: softmax scale folded into the K operand (see dkdv_role)
+#endif
+constexpr bool kFoldScale = BURST_FOLD_SCALE != 0;
 #ifndef BURST_DQ_KB
 #define BURST_DQ_KB 2   // 32-row key blocks per LDS tile of the dQ kernel
 #endif
@@ -158,38 +162,44 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_bwd_dq_kernel(B
 }
 
 // ---------------------------------------------------------------------------------------------
-// Eight waves per work-group, two per SIMD, in two roles that share each block of 32 key rows:
-//   P-wave  (waves 0-3): K rows in registers; S = Q K^T, P = exp2(..) -> bf16, hands P over through
-//                        LDS, then dV^T += dO^T P.  Also stages the next query tile.
-//   dS-wave (waves 4-7): V rows in registers; dP = dO V^T, then dS = P o (dP - D), dK^T += Q^T dS.
-// Each role carries one 32 x D accumulator and one stationary operand, which is what lets two
-// waves fit on a SIMD.  The dS-wave finishes a query tile one iteration late: in iteration t it
-// first turns the dP it kept in registers and the P of tile t-1 into dS and dK, and only then
-// computes dP of tile t, while the P-wave of the same SIMD runs S, softmax, dV of tile t and moves
-// tile t+1 from global memory to LDS.  One barrier per tile: everything a wave reads in iteration
-// t was written before the barrier that ended iteration t-1.
-//   LDS: Q tiles and D rows in three slots (tile t-1 for dK, t for S, t+1 being staged), dO tiles,
-//   lse rows and the P hand-over area in two.
-template <int D, int BQ>
+// dK/dV kernel.  Eight waves per work-group, two per SIMD, in two roles that share each block of 32 key rows:
+//   P-wave  (waves 0-3): K rows in registers; S = Q K^T, P = exp2(..) -> bf16, handed over through LDS,
+//                        dV^T += dO^T P.  Also stages the query tiles.
+//   dS-wave (waves 4-7): V rows in registers; dP = dO V^T - D, dS = P o dP, dK^T += Q^T dS.
+// Each role carries one 32 x D accumulator and one stationary operand, which is what lets two waves fit on a
+// SIMD; the two roles are separate instruction streams, register-allocated on their own.  Each stream is
+// software-pipelined: the vector work of one unit of 32 query rows is sliced behind the MFMAs of the next
+// unit, so both waves of a SIMD offer MFMAs to the matrix pipe nearly all the time:
+//   P-wave,  unit u:  S(u+1) = Q K^T  with the slices of P(u) = exp2(c S(u) - lse) behind its MFMAs,
+//                     then dV^T += dO^T P(u)  (its first MFMAs carry the last slices), P(u) -> LDS;
+//   dS-wave, unit u:  dP(u+1) = dO V^T - D  with the slices of dS(u) = P(u) o dP(u) behind its MFMAs,
+//                     then dK^T += Q^T dS(u).
+// Query tiles are 64 rows (two units, a and b).  One barrier per tile, which the P-waves pass between the two
+// units of tile t and the dS-waves before they start tile t: a dS-wave then works on dP of tile t and on dS / dK
+// of unit b of tile t-1 and unit a of tile t, whose P the P-waves wrote before that barrier.  Q tiles live in
+// four LDS slots (t-2 and t-1 for dK, t and t+1 for S, one of them being written), dO tiles, lse and -D rows in
+// three, the P hand-over area in two per unit.  The P-waves stage the tiles.
+template <int D>
 struct DkdvLds {
-  static constexpr int PITCH = 2 * D + 16, TILE = BQ * PITCH, QBK = BQ / 32;
-  static constexpr int Q_OFF = 0, DO_OFF = 3 * TILE, LSE_OFF = 5 * TILE, D_OFF = LSE_OFF + 2 * BQ * 4;
+  static constexpr int BQ = 64, PITCH = 2 * D + 16, TILE = BQ * PITCH;
+  static constexpr int Q_OFF = 0, DO_OFF = 4 * TILE, LSE_OFF = 7 * TILE, D_OFF = LSE_OFF + 3 * BQ * 4;
   static constexpr int P_OFF = D_OFF + 3 * BQ * 4;
-  static constexpr int P_SLOT = 4 * QBK * 2 * 64;          // bf16x8 units: [pair][qb][half][lane]
-  static constexpr int BYTES = P_OFF + 2 * P_SLOT * 16;
+  static constexpr int P_UNIT = 4 * 2 * 64;                // bf16x8 per unit: [pair][half][lane]
+  static constexpr int BYTES = P_OFF + 2 * 2 * P_UNIT * 16;   // [tile parity][unit]
 };
 
-template <int D, int BQ, int ROLE>
+template <int D, int ROLE>
 __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b, int hk, int kv_tile, int pair) {
-  constexpr int DK = D / 16, DB = D / 32, QBK = BQ / 32, BKV = 128, NT = 256;   // NT: staging threads
-  using L = DkdvLds<D, BQ>;
+  constexpr int DK = D / 16, DB = D / 32, BQ = 64, BKV = 128, NT = 256;
+  constexpr int PRE_R = kRowsAhead, PRE_C = kColsAhead;
+  using L = DkdvLds<D>;
   constexpr int PITCH = L::PITCH, TILE = L::TILE;
   float* lse_slots = reinterpret_cast<float*>(smem + L::LSE_OFF);
   float* d_slots = reinterpret_cast<float*>(smem + L::D_OFF);
   bf16x8* pbuf = reinterpret_cast<bf16x8*>(smem + L::P_OFF);
 
   const int group = p.q_heads / p.kv_heads;
-  const int tid = threadIdx.x & 255, lane = tid & 63, r = lane & 31, h = lane >> 5;   // tid within the role
+  const int tid = threadIdx.x & 255, lane = tid & 63, r = lane & 31, h = lane >> 5;
   const int sq = p.sq, sk = p.sk;
   const MaskDev mk = p.mask;
   const int k_blk0 = p.k_runs.tile_of(kv_tile) * BKV, k_blk1 = min(k_blk0 + BKV, sk);
@@ -205,46 +215,52 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
     for (int ks = 0; ks < DK; ++ks) xreg[ks] = *reinterpret_cast<const bf16x8*>(s_ + ks * 16);
   }
   const float c = p.scale * kLog2e;
+  if (ROLE == 0 && kFoldScale) {
+    // K rows carry the factor scale * log2(e) (rounded to bf16 once per work-group) and the S accumulators start
+    // from -lse: P = exp2 of the accumulator, no per-score multiply-add.  The extra rounding of K moves P by a
+    // few 1e-3 relative, the size of the bf16 rounding P undergoes anyway before the dV product (the paper
+    // fixes no precision); only this kernel does it: the forward kernel's Lse is held to 1e-3 absolute and
+    // keeps the exact multiply-add.
+#pragma unroll
+    for (int ks = 0; ks < DK; ++ks)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) xreg[ks][e] = (__bf16)((float)xreg[ks][e] * c);
+  }
 
   f32x16 acc[DB];   // dV^T (P-wave) or dK^T (dS-wave)
 #pragma unroll
   for (int db = 0; db < DB; ++db) zero16(acc[db]);
 
-  // Position ranges of the work-group's 128 key rows and of this pair's 32: loop invariants of the
-  // tile classification.
   int klo_blk, khi_blk, klo_w = 0, khi_w = 0;
   range_minmax<false>(mk, k_blk0, k_blk1, klo_blk, khi_blk);
   const bool has_keys = k_w0 < k_w1;
   if (has_keys) range_minmax<false>(mk, k_w0, k_w1, klo_w, khi_w);
-  // Class of a whole query tile against this pair's 32 key rows (same for both waves of the pair).
-  // A tile the mask only partly empties is computed whole with the per-element predicate.
+  // A tile runs under the per-element predicate unless all of it is visible to this pair's keys; tiles that
+  // are empty for this pair alone do too (their P is 0), so that the pipeline has no per-wave holes.
   BlockClassifier<true> q_class;
   q_class.init(mk, klo_w, khi_w, sq, !has_keys);
-  auto tile_class = [&](int q0) { return q_class(mk, q0, min(q0 + BQ, sq), q0 + BQ > sq); };
+  auto tile_masked = [&](int q0_) { return q_class(mk, q0_, min(q0_ + BQ, sq), q0_ + BQ > sq) != TILE_FULL; };
 
-  // Walk over (query head of the group, query tile that can see the key block), flattened so the
-  // pipeline runs across head boundaries.  The visible tiles of a head are one run of consecutive
-  // tiles; inside it the cursor moves by adding constants, and only a head change recomputes addresses.
+  // Walk over (query head of the group, query tile that can see the key block) as one sequence; both roles
+  // move the same cursor, only the P-waves load.
   const TileRun qr = visible_tiles<true, BQ>(mk, klo_blk, khi_blk, sq);
-  bool c_valid = qr.len > 0;                       // the cursor is on an item
-  int c_left = qr.len, c_head = 0;                 // cursor: tiles left in the head's run, head of the group
-  int q0n = qr.start * BQ;                         // first row of the tile under the cursor
+  bool c_valid = qr.len > 0;
+  int c_left = qr.len, c_head = 0;
+  int q0n = qr.start * BQ;
 
-  TileStager<D, BQ, NT> stage_q, stage_do;         // P-wave only
-  float stage_row = 0.f;   // threads [0, BQ): lse of a row; threads [BQ, 2*BQ): D of a row
-  const char *q_tile = nullptr, *do_tile = nullptr;   // first row of the tile under the cursor
-  const float* row_head = nullptr;                    // lse (threads < BQ) or D of the cursor's head
+  TileStager<D, BQ, NT> stage_q, stage_do;   // P-wave only
+  float stage_row = 0.f;
+  const char *q_tile = nullptr, *do_tile = nullptr;
+  const float* row_head = nullptr;
   const int64_t q_step = (int64_t)BQ * p.q.ss * 2, do_step = (int64_t)BQ * p.d_o.ss * 2;
   if (ROLE == 0) {
     stage_q.init(p.q.ss, tid);
     stage_do.init(p.d_o.ss, tid);
   }
-  // which row vector this thread stages (selected once: a select between pointers inside the walk ends up
-  // as an indexed array in scratch memory)
   const bool stages_lse = tid < BQ;
   const float* const rowvec_ptr = stages_lse ? p.lse.ptr : p.d.ptr;
   const int64_t rowvec_sb = stages_lse ? p.lse.sb : p.d.sb, rowvec_sh = stages_lse ? p.lse.sh : p.d.sh;
-  auto point = [&]() {   // addresses of the tile under the cursor, from scratch
+  auto point = [&]() {
     if (ROLE != 0) return;
     const int hq = hk * group + c_head;
     q_tile = reinterpret_cast<const char*>((const __bf16*)p.q.ptr + b * p.q.sb + hq * p.q.sh + (int64_t)q0n * p.q.ss);
@@ -252,7 +268,6 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
                                             (int64_t)q0n * p.d_o.ss);
     row_head = rowvec_ptr + b * rowvec_sb + hq * rowvec_sh;
   };
-  // Open flags of the query tiles against this work-group's key block (block-wise sparse mask)
   const uint8_t* open_flags = nullptr;
   if (mk.blk) {
     uint8_t* flags = reinterpret_cast<uint8_t*>(smem + L::BYTES);
@@ -261,7 +276,7 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
     __syncthreads();
   }
   auto is_open = [&](int q0_) { return !open_flags || __builtin_amdgcn_readfirstlane(open_flags[q0_ / BQ]) != 0; };
-  auto step = [&]() {   // cursor to the next tile of the walk
+  auto step = [&]() {
     if (--c_left > 0) {
       q0n += BQ;
       q_tile += q_step;
@@ -274,128 +289,217 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
       else c_valid = false;
     }
   };
-  auto advance = [&]() {   // cursor to the next item: the next tile that the block mask leaves open
+  auto advance = [&]() {
     do step();
     while (c_valid && !is_open(q0n));
   };
-  auto issue = [&]() {   // loads of the tile under the cursor
+  auto issue = [&]() {
     if (ROLE != 0) return;
     if (q0n + BQ <= sq) {
       stage_q.load_at(q_tile);
       stage_do.load_at(do_tile);
-    } else {   // last tile of a ragged chunk: row indices clamped per thread
+    } else {
       stage_q.load(reinterpret_cast<const __bf16*>(q_tile) - (int64_t)q0n * p.q.ss, p.q.ss, q0n, sq, tid);
       stage_do.load(reinterpret_cast<const __bf16*>(do_tile) - (int64_t)q0n * p.d_o.ss, p.d_o.ss, q0n, sq, tid);
     }
-    // raw value only: converting here would wait for this load, and with it for the tile loads
     if (tid < 2 * BQ) stage_row = row_head[min(q0n + (tid & (BQ - 1)), sq - 1)];
   };
-  auto commit = [&](int q_slot, int par) {   // q_slot: Q / D slot, par: dO / lse slot
+  auto commit = [&](int q_slot, int o_slot) {
     if (ROLE != 0) return;
     stage_q.store(smem + L::Q_OFF + q_slot * TILE);
-    stage_do.store(smem + L::DO_OFF + par * TILE);
-    if (tid < BQ) lse_slots[par * BQ + tid] = lse_to_log2(stage_row);
-    else if (tid < 2 * BQ) d_slots[q_slot * BQ + tid - BQ] = -stage_row;   // -D: the dS-wave's dP accumulators start from it
+    stage_do.store(smem + L::DO_OFF + o_slot * TILE);
+    if (tid < BQ) lse_slots[o_slot * BQ + tid] = kFoldScale ? -lse_to_log2(stage_row) : lse_to_log2(stage_row);
+    else if (tid < 2 * BQ) d_slots[o_slot * BQ + tid - BQ] = -stage_row;   // -D: the dP accumulators start from it
   };
 
   wait_global_loads();
-  int q0 = 0, cls = TILE_SKIP;   // first row and class of the tile in slot (qs_cur, par)
   if (c_valid) {
     point();
     if (!is_open(q0n)) advance();
   }
-  bool have = c_valid;
-  if (have) {
+  if (c_valid) {   // uniform over the work-group: both roles take the same number of barriers
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    // 16 per-row values of a unit (rows 8g + 4h + j of its 32) from an LDS row vector
+    auto rows16 = [&](const float* vec, f32x16& out) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x4 x = *reinterpret_cast<const f32x4*>(vec + 8 * g + 4 * h);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[4 * g + j] = x[j];
+      }
+    };
+    auto words_to_operand = [&](const uint32_t (&w)[8], int half) {
+      const u32x4 x = {w[4 * half], w[4 * half + 1], w[4 * half + 2], w[4 * half + 3]};
+      return __builtin_bit_cast(bf16x8, x);
+    };
+    // Values of a lane's 16 that go behind slot j of the first stream of a unit (DK MFMAs: values 0..11) and of
+    // the first DB MFMAs of the second (values 12..15): the second stream's chunk 0 needs values 0..7 only.
+    auto first_lo = [](int j) { return 12 * j / DK; };
+    auto second_lo = [](int j) { return 12 + 4 * j / DB; };
+    const int p_lane = pair * 2 * 64 + lane;   // this pair's place inside a unit of the hand-over area
+
+    // cursor bookkeeping shared by the roles
     issue();
     commit(0, 0);
-    q0 = q0n;
-    cls = tile_class(q0n);
+    int q0_cur = q0n;
+    bool msk_cur = tile_masked(q0n);
     advance();
-  }
-  __syncthreads();
-  int qs_prev = 2, qs_cur = 0, qs_next = 1, par = 0;
-  int cls_prev = TILE_SKIP;
-  f32x16 dp[QBK];   // dS-wave: dP of the tile staged one iteration ago
-  // one iteration per item and a last one that only drains the dS-wave's lagging half
-  for (;;) {
-    const bool more = have && c_valid;
-    int q0_next = 0, cls_next = TILE_SKIP;
+    bool more = c_valid;
+    int q0_nxt = 0;
+    bool msk_nxt = false;
     if (more) {
       issue();
-      q0_next = q0n;
-      cls_next = tile_class(q0n);
+      q0_nxt = q0n;
+      msk_nxt = tile_masked(q0n);
       advance();
     }
-    const char* dot_ = smem + L::DO_OFF + par * TILE;
+    __syncthreads();   // tile 0 is in LDS
+    int qs = 0, os = 0, par = 0;   // Q slot, dO / row slot and hand-over parity of the current tile
+
     if (ROLE == 0) {
-      if (cls != TILE_SKIP) {
-        const char* qt_ = smem + L::Q_OFF + qs_cur * TILE;
-        const float* lse2 = lse_slots + par * BQ;
-        bf16x8* pw = pbuf + par * L::P_SLOT;
-        bf16x8 pk[2 * QBK];
-        f32x16 s[QBK];
-        gemm_rows<PITCH, QBK, DK, kRowsAhead, true>(qt_, 0, xreg, s, r, h);   // first MFMA of each block adds to a literal zero
+      f32x16 s0, s1, l2;
+      uint32_t pw[8];
+      bf16x8 pk[2];
+      // P(u) slices: values [v0, v1) of tile s
+      auto p_vals = [&](f32x16& s, int v0, int v1) {
 #pragma unroll
-        for (int qb = 0; qb < QBK; ++qb) {
-          if (cls == TILE_PARTIAL) mask_tile<false>(s[qb], mk, q0 + qb * 32, h, sq, kpos);
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse2 + qb * 32 + 8 * g + 4 * h);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) s[qb][4 * g + j] = __builtin_amdgcn_exp2f(c * s[qb][4 * g + j] - l4[j]);
+        for (int v = 0; v < 16; ++v) {
+          if (v < v0 || v >= v1) continue;
+          s[v] = kFoldScale ? __builtin_amdgcn_exp2f(s[v]) : __builtin_amdgcn_exp2f(c * s[v] - l2[v]);
+          if (v & 1) {
+            const bf16x2 pr = {(__bf16)s[v - 1], (__bf16)s[v]};
+            pw[v >> 1] = __builtin_bit_cast(uint32_t, pr);
           }
-          pk[2 * qb] = pack8(s[qb], 0);
-          pk[2 * qb + 1] = pack8(s[qb], 1);
-          pw[((pair * QBK + qb) * 2 + 0) * 64 + lane] = pk[2 * qb];
-          pw[((pair * QBK + qb) * 2 + 1) * 64 + lane] = pk[2 * qb + 1];
         }
-        gemm_cols<PITCH, DB, 2 * QBK, kColsAhead>(dot_, 0, pk, acc, lane);
+      };
+      // second half of a unit: dV^T += dO^T P with the last slices and the hand-over store behind its MFMAs
+      auto dv_stream = [&](f32x16& s, int o_slot, int row0, int unit) {
+        pk[0] = words_to_operand(pw, 0);
+        pk[1] = pk[0];   // placeholder until the hooks below have produced values 8..15
+        bf16x8* dst = pbuf + (par * 2 + unit) * L::P_UNIT + p_lane;
+        cols_stream<PITCH, DB, 2, PRE_C>(smem + L::DO_OFF + o_slot * TILE, row0, pk, acc, lane, [&](int i) {
+          if (i < DB) p_vals(s, second_lo(i), second_lo(i + 1));
+          if (i == DB - 1) pk[1] = words_to_operand(pw, 1);
+          if (i == DB) dst[0] = pk[0];
+          if (i == DB + 1) dst[64] = pk[1];
+        });
+      };
+      // S of the unit at rows row0 of the tile in (q_slot, o_slot) with hook(j) behind MFMA j
+      auto s_stream = [&](f32x16& s, int q_slot, int o_slot, int row0, auto&& hook) {
+        if (kFoldScale) {
+          rows16(lse_slots + o_slot * BQ + row0, s);
+          rows_stream<PITCH, DK, PRE_R, false>(smem + L::Q_OFF + q_slot * TILE, row0, xreg, s, r, h, hook);
+        } else {
+          rows_stream<PITCH, DK, PRE_R, true>(smem + L::Q_OFF + q_slot * TILE, row0, xreg, s, r, h, hook);
+        }
+      };
+      s_stream(s0, 0, 0, 0, NoHook());
+      for (;;) {
+        const int qs1 = (qs + 1) & 3, os1 = os == 2 ? 0 : os + 1;
+        // unit a of the tile (s0); S of unit b is produced meanwhile (s1)
+        if (!kFoldScale) rows16(lse_slots + os * BQ, l2);
+        if (msk_cur) mask_tile<false>(s0, mk, q0_cur, h, sq, kpos);
+        s_stream(s1, qs, os, 32, [&](int j) { p_vals(s0, first_lo(j), first_lo(j + 1)); });
+        dv_stream(s0, os, 0, 0);
+        if (more) commit(qs1, os1);
+        __syncthreads();
+        const bool more2 = more && c_valid;
+        int q0_n2 = 0;
+        bool msk_n2 = false;
+        if (more2) {
+          issue();
+          q0_n2 = q0n;
+          msk_n2 = tile_masked(q0n);
+          advance();
+        }
+        // unit b (s1); S of the next tile's unit a is produced meanwhile (s0)
+        if (!kFoldScale) rows16(lse_slots + os * BQ + 32, l2);
+        if (msk_cur) mask_tile<false>(s1, mk, q0_cur + 32, h, sq, kpos);
+        if (more) {
+          s_stream(s0, qs1, os1, 0, [&](int j) { p_vals(s1, first_lo(j), first_lo(j + 1)); });
+        } else {
+          p_vals(s1, 0, 12);
+        }
+        dv_stream(s1, os, 32, 1);
+        if (!more) break;
+        qs = qs1;
+        os = os1;
+        par ^= 1;
+        q0_cur = q0_nxt;
+        msk_cur = msk_nxt;
+        q0_nxt = q0_n2;
+        msk_nxt = msk_n2;
+        more = more2;
       }
+      __syncthreads();   // the last unit's P is in LDS
     } else {
-      if (cls_prev != TILE_SKIP) {
-        const char* qt_ = smem + L::Q_OFF + qs_prev * TILE;
-        const bf16x8* pr_ = pbuf + (par ^ 1) * L::P_SLOT;
-        bf16x8 dsp[2 * QBK];
+      f32x16 dpa, dpb;   // dP - D of unit a / unit b
+      uint32_t dw[8];
+      bf16x8 dsk[2], p0, p1;
+      // dS(u) slices: values [v0, v1) from the P words p0 / p1 and the dP - D tile
+      auto ds_vals = [&](f32x16& dpv, int v0, int v1) {
 #pragma unroll
-        for (int qb = 0; qb < QBK; ++qb) {
-          const bf16x8 p0 = pr_[((pair * QBK + qb) * 2 + 0) * 64 + lane];
-          const bf16x8 p1 = pr_[((pair * QBK + qb) * 2 + 1) * 64 + lane];
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const float pr = (float)(v < 8 ? p0[v & 7] : p1[v & 7]);
-            dp[qb][v] = pr * dp[qb][v];   // dp already holds dP - D
+        for (int v = 0; v < 16; ++v) {
+          if (v < v0 || v >= v1) continue;
+          const float pr = (float)(v < 8 ? p0[v & 7] : p1[v & 7]);
+          dpv[v] = pr * dpv[v];
+          if (v & 1) {
+            const bf16x2 x = {(__bf16)dpv[v - 1], (__bf16)dpv[v]};
+            dw[v >> 1] = __builtin_bit_cast(uint32_t, x);
           }
-          dsp[2 * qb] = pack8(dp[qb], 0);
-          dsp[2 * qb + 1] = pack8(dp[qb], 1);
         }
-        gemm_cols<PITCH, DB, 2 * QBK, kColsAhead>(qt_, 0, dsp, acc, lane);
+      };
+      auto load_p = [&](int parity, int unit) {
+        const bf16x8* src = pbuf + (parity * 2 + unit) * L::P_UNIT + p_lane;
+        p0 = src[0];
+        p1 = src[64];
+      };
+      // dP - D of the unit at rows row0 of the tile in o_slot, with dS slices of tile `dsv` behind its MFMAs
+      auto dp_stream = [&](f32x16& dpv, int o_slot, int row0, f32x16* dsv) {
+        rows16(d_slots + o_slot * BQ + row0, dpv);
+        if (dsv) {
+          rows_stream<PITCH, DK, PRE_R, false>(smem + L::DO_OFF + o_slot * TILE, row0, xreg, dpv, r, h,
+                                                    [&](int j) { ds_vals(*dsv, first_lo(j), first_lo(j + 1)); });
+        } else {
+          rows_stream<PITCH, DK, PRE_R, false>(smem + L::DO_OFF + o_slot * TILE, row0, xreg, dpv, r, h);
+        }
+      };
+      auto dk_stream = [&](f32x16& dsv, int q_slot, int row0) {
+        dsk[0] = words_to_operand(dw, 0);
+        dsk[1] = dsk[0];
+        cols_stream<PITCH, DB, 2, PRE_C>(smem + L::Q_OFF + q_slot * TILE, row0, dsk, acc, lane, [&](int i) {
+          if (i < DB) ds_vals(dsv, second_lo(i), second_lo(i + 1));
+          if (i == DB - 1) dsk[1] = words_to_operand(dw, 1);
+        });
+      };
+      bool first = true;
+      for (;;) {
+        __syncthreads();   // P of unit a of this tile and of unit b of the previous one is in LDS
+        const int qs1 = (qs + 1) & 3, os1 = os == 2 ? 0 : os + 1;
+        const bool more2 = more && c_valid;
+        if (more2) advance();
+        if (!first) {
+          load_p(par ^ 1, 1);
+          dp_stream(dpa, os, 0, &dpb);
+          dk_stream(dpb, (qs + 3) & 3, 32);
+        } else {
+          dp_stream(dpa, os, 0, nullptr);
+        }
+        load_p(par, 0);
+        dp_stream(dpb, os, 32, &dpa);
+        dk_stream(dpa, qs, 0);
+        first = false;
+        if (!more) break;
+        qs = qs1;
+        os = os1;
+        par ^= 1;
+        more = more2;
       }
-      if (cls != TILE_SKIP) {
-        // dP - D: the accumulators start from -D of their query rows (registers run over rows here)
-        const float* nd_ = d_slots + qs_cur * BQ;
-#pragma unroll
-        for (int qb = 0; qb < QBK; ++qb)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const f32x4 d4 = *reinterpret_cast<const f32x4*>(nd_ + qb * 32 + 8 * g + 4 * h);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) dp[qb][4 * g + j] = d4[j];
-          }
-        gemm_rows<PITCH, QBK, DK, kRowsAhead>(dot_, 0, xreg, dp, r, h);
-      }
+      __syncthreads();
+      load_p(par, 1);
+      ds_vals(dpb, 0, 12);
+      dk_stream(dpb, qs, 32);
     }
-    if (more) commit(qs_next, par ^ 1);
-    __syncthreads();
-    const int t_ = qs_prev;
-    qs_prev = qs_cur;
-    qs_cur = qs_next;
-    qs_next = t_;
-    par ^= 1;
-    cls_prev = cls;
-    q0 = q0_next;
-    cls = cls_next;
-    if (!have) break;
-    have = more;
   }
 
   if (k_w0 + r < sk) {
@@ -415,17 +519,15 @@ __device__ __forceinline__ void dkdv_role(const BwdParams& p, char* smem, int b,
   }
 }
 
-template <int D, int BQ>
+template <int D>
 __global__ __launch_bounds__(512, 1) void step_bwd_dkdv_kernel(BwdParams p) {
   extern __shared__ __attribute__((aligned(16))) char smem[];   // laid out by DkdvLds
   const BlockMap bm = map_block<false>(blockIdx.x, p.batch * p.kv_heads, 1, p.k_runs.total());
   if (!bm.valid) return;
   const int b = bm.key / p.kv_heads, hk = bm.key - b * p.kv_heads;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: the role branch is uniform
-  // Two complete, separate instruction streams (same barrier count per tile in both), so that each
-  // role is register-allocated on its own.
-  if (wave < 4) dkdv_role<D, BQ, 0>(p, smem, b, hk, bm.tile, wave);
-  else dkdv_role<D, BQ, 1>(p, smem, b, hk, bm.tile, wave - 4);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (wave < 4) dkdv_role<D, 0>(p, smem, b, hk, bm.tile, wave);
+  else dkdv_role<D, 1>(p, smem, b, hk, bm.tile, wave - 4);
 }
 
 template <int D>
@@ -449,8 +551,8 @@ static hipError_t launch_bwd_t(BwdParams p, hipStream_t stream) {
     }
   }
   if (p.dk.ptr) {
-    constexpr int BQ = 64;
-    constexpr int LDS = DkdvLds<D, BQ>::BYTES + kMaxBlockCacheTiles;
+    constexpr int LDS = DkdvLds<D>::BYTES + kMaxBlockCacheTiles;
+    static_assert(LDS <= 160 * 1024, "LDS of a CU");
     p.k_runs = nonempty_runs(p.mask, p.sq, p.sk, 128, false);
     if (p.k_runs.total() < (p.sk + 127) / 128) {
       if (!p.acc_dk) e = launch_zero_tensor(p.dk, p.batch, p.sk, p.kv_heads, p.head_dim, stream);
@@ -459,7 +561,7 @@ static hipError_t launch_bwd_t(BwdParams p, hipStream_t stream) {
     }
     if (p.k_runs.total() > 0) {
       const int grid = mapped_grid(n_keys, 1, p.k_runs.total());
-      hipLaunchKernelGGL((step_bwd_dkdv_kernel<D, BQ>), dim3(grid), dim3(512), LDS, stream, p);
+      hipLaunchKernelGGL((step_bwd_dkdv_kernel<D>), dim3(grid), dim3(512), LDS, stream, p);
       e = hipGetLastError();
       if (e != hipSuccess) return e;
     }

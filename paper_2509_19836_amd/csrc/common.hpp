@@ -546,6 +546,43 @@ __device__ __forceinline__ void gemm_cols_run(const char* tile, int row0, const 
   }
 }
 
+// Streams with one hook per MFMA, for software-pipelined kernels: hook(i) holds the few vector or LDS
+// instructions of ANOTHER unit of work that go behind MFMA i, and the scheduling fence after it keeps them
+// there, so that a wave's vector work runs in the shadow of matrix work that does not depend on it.
+//   acc (+)= rows(tile)[row0 .. row0+31] * b   (ZERO: starts from a literal zero)
+template <int PITCH, int DK, int PRE, bool ZERO, class Hook = NoHook>
+__device__ __forceinline__ void rows_stream(const char* tile, int row0, const bf16x8 (&b)[DK], f32x16& acc, int r, int h,
+                                            Hook&& hook = Hook()) {
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  bf16x8 a[DK];
+#pragma unroll
+  for (int ks = 0; ks < PRE && ks < DK; ++ks) a[ks] = lds_rows_operand<PITCH>(tile, row0, ks * 16, r, h);
+#pragma unroll
+  for (int ks = 0; ks < DK; ++ks) {
+    if (ks + PRE < DK) a[ks + PRE] = lds_rows_operand<PITCH>(tile, row0, (ks + PRE) * 16, r, h);
+    acc = mfma32(a[ks], b[ks], (ZERO && ks == 0) ? zero : acc);
+    hook(ks);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+//   acc[db] += cols(tile)[db, c] * b[c]  (as gemm_cols), hook(i) behind MFMA i = c * DB + db; b is read when
+//   its MFMA is issued, so a hook may still complete b[c] for a later chunk c.
+template <int PITCH, int DB, int NC, int PRE, class Hook = NoHook>
+__device__ __forceinline__ void cols_stream(const char* tile, int row0, const bf16x8 (&b)[NC], f32x16 (&acc)[DB], int lane,
+                                            Hook&& hook = Hook()) {
+  constexpr int N = NC * DB;
+  bf16x8 a[N];
+#pragma unroll
+  for (int i = 0; i < PRE && i < N; ++i) a[i] = lds_cols_operand<PITCH>(tile, row0 + 16 * (i / DB), (i % DB) * 32, lane);
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    if (i + PRE < N) a[i + PRE] = lds_cols_operand<PITCH>(tile, row0 + 16 * ((i + PRE) / DB), ((i + PRE) % DB) * 32, lane);
+    acc[i % DB] = mfma32(a[i], b[i / DB], acc[i % DB]);
+    hook(i);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 __device__ __forceinline__ bf16x8 pack8(const f32x16& x, int c) {
   bf16x8 o;
 #pragma unroll
