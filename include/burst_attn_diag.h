@@ -36,6 +36,12 @@ int burst_attn_visible_tile_runs(const burst_mask_t* mask, int32_t query_axis, i
 int burst_attn_mfma_probe(int32_t random_operands, int32_t iterations, float* sink, int64_t* flops_out,
                           void* hip_stream);
 
+/* The backward kernels cut a streamed axis (keys for dQ, queries for dK / dV) that is longer than twice
+ * `rows` into ranges of about `rows` rows, one launch per range (an L2-locality measure; default 32768).
+ * Tests lower it to drive the chunked path at sizes the oracle can check exhaustively.  Process-wide;
+ * values below 256 are raised to 256.  Returns the value now in force. */
+int burst_attn_set_bwd_chunk_rows(int32_t rows);
+
 #ifdef __cplusplus
 }
 #endif

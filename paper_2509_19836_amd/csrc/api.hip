@@ -480,6 +480,11 @@ int burst_attn_visible_tile_runs(const burst_mask_t* mask, int32_t query_axis, i
   return BURST_OK;
 }
 
+int burst_attn_set_bwd_chunk_rows(int32_t rows) {
+  burst::set_bwd_chunk_rows(rows);
+  return rows < 256 ? 256 : rows;
+}
+
 int burst_attn_mfma_probe(int32_t random_operands, int32_t iterations, float* sink, int64_t* flops_out,
                           void* hip_stream) {
   if (iterations < 1 || iterations > (1 << 24)) return BURST_ERR_INVALID_ARG;

@@ -106,6 +106,8 @@ hipError_t launch_lm_head_loss(const LmHeadParams& p, hipStream_t stream);
 
 hipError_t launch_step_fwd(const FwdParams& p, hipStream_t stream);
 hipError_t launch_step_bwd(const BwdParams& p, hipStream_t stream);
+// rows of the streamed axis per launch of a backward kernel (longer axes are cut into several launches)
+void set_bwd_chunk_rows(int rows);
 hipError_t launch_lse_merge(const MergeParams& p, hipStream_t stream);
 hipError_t launch_preprocess_bwd(const PreParams& p, hipStream_t stream);
 // o_part = 0 / lse_part = -inf for a step with no key rows; zero-fill of fp32 gradients
