@@ -22,13 +22,15 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
 
-# HBM bytes per launch of the dominant kernel from the FETCH_SIZE / WRITE_SIZE counter runs of this
-# command (counter means over the ring, scaled by what the same counters read for the 1 GiB copy issued
-# below).  Counters cannot be read from inside the process, so the figure is the profiled one: it is
-# reported with the profile it came from and its date, and only for the workload that was profiled.
+# HBM bytes per ring step of the dominant kernel from the FETCH_SIZE / WRITE_SIZE counter runs of this
+# command (counter sums over the kernel's launches of a ring, divided by its steps, scaled by what the same
+# counters read for the 1 GiB copy issued below; at shards beyond 65536 rows a step is several launches of
+# the kernel, one per 32768-row range of the streamed axis).  Counters cannot be read from inside the
+# process, so the figure is the profiled one: it is reported with the profile it came from and its date,
+# and only for the workload that was profiled.
 PROFILED_TRAFFIC = {
-    2: {"bytes": 1.922e9, "profile": "profiles/bench_config2_pmc_hbm_traffic.md", "taken": "2026-11-27, same dK/dV kernel"},
-    5: {"bytes": 3.387e11, "profile": "profiles/bench_config5_pmc_hbm_traffic.md", "taken": "2026-11-28, same dK/dV kernel"},
+    2: {"bytes": 1.985e9, "profile": "profiles/bench_config2_pmc_hbm_traffic.md", "taken": "2026-11-28, this dK/dV kernel"},
+    5: {"bytes": 2.059e11, "profile": "profiles/bench_config5_pmc_hbm_traffic.md", "taken": "2026-11-28, this dK/dV kernel"},
 }
 # --lm-head, default shape: bytes per call over all its launches (profiles/bench_lm_head_kernel_trace_and_counters.md)
 PROFILED_LM_HEAD_TRAFFIC_BYTES = 2.73e10
