@@ -42,6 +42,14 @@ int burst_attn_mfma_probe(int32_t random_operands, int32_t iterations, float* si
  * values below 256 are raised to 256.  Returns the value now in force. */
 int burst_attn_set_bwd_chunk_rows(int32_t rows);
 
+/* Host view of that plan (no GPU involved): the ranges of local rows the query axis (query_axis != 0: the
+ * dK/dV kernel's launches) or the key axis (the dQ kernel's) of a step with this mask is cut into.  Returns
+ * the number of ranges (negative burst_status_t on a bad mask) and fills, for the first max_ranges of them,
+ * out[7 i ..] = {first row, end row, pieces, rows per piece, position of the first row, position period of
+ * the pieces, byte offset of the range's block mask from the step's} -- the chunk the range's launch
+ * describes to the kernel.  One range means one launch with the step's own mask. */
+int burst_attn_bwd_chunk_plan(const burst_mask_t* mask, int32_t query_axis, int32_t max_ranges, int64_t* out);
+
 #ifdef __cplusplus
 }
 #endif

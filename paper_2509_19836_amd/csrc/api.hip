@@ -485,6 +485,14 @@ int burst_attn_set_bwd_chunk_rows(int32_t rows) {
   return rows < 256 ? 256 : rows;
 }
 
+int burst_attn_bwd_chunk_plan(const burst_mask_t* mask, int32_t query_axis, int32_t max_ranges, int64_t* out) {
+  if (!mask || !out || max_ranges < 0 || mask->q_nseg < 1 || mask->k_nseg < 1) return BURST_ERR_INVALID_ARG;
+  const int64_t sq = mask->q_nseg * mask->q_seg_len, sk = mask->k_nseg * mask->k_seg_len;
+  MaskDev mk;
+  BURST_TRY(check_mask(mask, sq, sk, &mk));
+  return bwd_chunk_plan(mk, (int)sq, (int)sk, query_axis != 0, max_ranges, out);
+}
+
 int burst_attn_mfma_probe(int32_t random_operands, int32_t iterations, float* sink, int64_t* flops_out,
                           void* hip_stream) {
   if (iterations < 1 || iterations > (1 << 24)) return BURST_ERR_INVALID_ARG;

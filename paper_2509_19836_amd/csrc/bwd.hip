@@ -672,6 +672,27 @@ static hipError_t launch_bwd_t(const BwdParams& p0, hipStream_t stream) {
   return hipSuccess;
 }
 
+// Host view of the launcher's plan for tests: the ranges the query axis (dK/dV kernel) or the key axis (dQ
+// kernel) of a step is cut into, each with the piece description of its sub-mask and the block-mask offset.
+int bwd_chunk_plan(const MaskDev& mk, int sq, int sk, bool query_axis, int max_ranges, int64_t* out) {
+  const std::vector<RowRange> ranges = query_axis ? chunk_ranges(mk.q_nseg, mk.q_seg_len, sq, mk.blk ? mk.blk_q : 0)
+                                                  : chunk_ranges(mk.k_nseg, mk.k_seg_len, sk, mk.blk ? mk.blk_k : 0);
+  int n = 0;
+  for (const RowRange& rg : ranges) {
+    if (n == max_ranges) break;
+    const MaskDev m = ranges.size() > 1 ? (query_axis ? sub_mask<true>(mk, rg.r0, rg.r1) : sub_mask<false>(mk, rg.r0, rg.r1)) : mk;
+    int64_t* o = out + 7 * n++;
+    o[0] = rg.r0;
+    o[1] = rg.r1;
+    o[2] = query_axis ? m.q_nseg : m.k_nseg;
+    o[3] = query_axis ? m.q_seg_len : m.k_seg_len;
+    o[4] = query_axis ? m.q_pos0 : m.k_pos0;
+    o[5] = query_axis ? m.q_period : m.k_period;
+    o[6] = m.blk ? (int64_t)(m.blk - mk.blk) : 0;
+  }
+  return (int)ranges.size();
+}
+
 hipError_t launch_step_bwd(const BwdParams& p, hipStream_t stream) {
   if (p.head_dim == 128) return launch_bwd_t<128>(p, stream);
   return launch_bwd_t<64>(p, stream);

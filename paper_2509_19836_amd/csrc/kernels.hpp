@@ -108,6 +108,7 @@ hipError_t launch_step_fwd(const FwdParams& p, hipStream_t stream);
 hipError_t launch_step_bwd(const BwdParams& p, hipStream_t stream);
 // rows of the streamed axis per launch of a backward kernel (longer axes are cut into several launches)
 void set_bwd_chunk_rows(int rows);
+int bwd_chunk_plan(const MaskDev& mk, int sq, int sk, bool query_axis, int max_ranges, int64_t* out);
 hipError_t launch_lse_merge(const MergeParams& p, hipStream_t stream);
 hipError_t launch_preprocess_bwd(const PreParams& p, hipStream_t stream);
 // o_part = 0 / lse_part = -inf for a step with no key rows; zero-fill of fp32 gradients
