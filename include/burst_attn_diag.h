@@ -36,19 +36,20 @@ int burst_attn_visible_tile_runs(const burst_mask_t* mask, int32_t query_axis, i
 int burst_attn_mfma_probe(int32_t random_operands, int32_t iterations, float* sink, int64_t* flops_out,
                           void* hip_stream);
 
-/* The backward kernels cut a streamed axis (keys for dQ, queries for dK / dV) that is longer than twice
- * `rows` into ranges of about `rows` rows, one launch per range (an L2-locality measure; default 32768).
- * Tests lower it to drive the chunked path at sizes the oracle can check exhaustively.  Process-wide;
- * values below 256 are raised to 256.  Returns the value now in force. */
-int burst_attn_set_bwd_chunk_rows(int32_t rows);
+/* The step kernels cut a streamed axis (keys for the forward kernel when it only updates the running state,
+ * and for dQ; queries for dK / dV) that is longer than twice `rows` into ranges of about `rows` rows, one
+ * launch per range (an L2-locality measure; default 32768).  Tests lower it to drive the chunked path at sizes
+ * the oracle can check exhaustively.  Process-wide; values below 256 are raised to 256.  Returns the value now
+ * in force. */
+int burst_attn_set_chunk_rows(int32_t rows);
 
 /* Host view of that plan (no GPU involved): the ranges of local rows the query axis (query_axis != 0: the
- * dK/dV kernel's launches) or the key axis (the dQ kernel's) of a step with this mask is cut into.  Returns
+ * dK/dV kernel's launches) or the key axis (the dQ kernel's and the forward kernel's) of a step with this mask is cut into.  Returns
  * the number of ranges (negative burst_status_t on a bad mask) and fills, for the first max_ranges of them,
  * out[7 i ..] = {first row, end row, pieces, rows per piece, position of the first row, position period of
  * the pieces, byte offset of the range's block mask from the step's} -- the chunk the range's launch
  * describes to the kernel.  One range means one launch with the step's own mask. */
-int burst_attn_bwd_chunk_plan(const burst_mask_t* mask, int32_t query_axis, int32_t max_ranges, int64_t* out);
+int burst_attn_chunk_plan(const burst_mask_t* mask, int32_t query_axis, int32_t max_ranges, int64_t* out);
 
 #ifdef __cplusplus
 }

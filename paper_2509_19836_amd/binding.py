@@ -72,10 +72,10 @@ _lib.burst_attn_tile_class.restype = C.c_int
 _lib.burst_attn_tile_class.argtypes = [_P(burst_mask_t)] + [C.c_int64] * 4 + [C.c_int32]
 _lib.burst_attn_visible_tile_runs.restype = C.c_int
 _lib.burst_attn_visible_tile_runs.argtypes = [_P(burst_mask_t), C.c_int32, C.c_int32, C.c_int64, C.c_int64, _P(C.c_int32 * 4)]
-_lib.burst_attn_set_bwd_chunk_rows.restype = C.c_int
-_lib.burst_attn_set_bwd_chunk_rows.argtypes = [C.c_int32]
-_lib.burst_attn_bwd_chunk_plan.restype = C.c_int
-_lib.burst_attn_bwd_chunk_plan.argtypes = [_P(burst_mask_t), C.c_int32, C.c_int32, _P(C.c_int64)]
+_lib.burst_attn_set_chunk_rows.restype = C.c_int
+_lib.burst_attn_set_chunk_rows.argtypes = [C.c_int32]
+_lib.burst_attn_chunk_plan.restype = C.c_int
+_lib.burst_attn_chunk_plan.argtypes = [_P(burst_mask_t), C.c_int32, C.c_int32, _P(C.c_int64)]
 _lib.burst_attn_mfma_probe.restype = C.c_int
 _lib.burst_attn_mfma_probe.argtypes = [C.c_int32, C.c_int32, C.c_void_p, _P(C.c_int64), C.c_void_p]
 
@@ -105,7 +105,7 @@ _lib.burst_attn_version.restype = C.c_char_p
 EXPORTS = ["burst_attn_step_fwd", "burst_attn_lse_merge", "burst_attn_preprocess_bwd", "burst_attn_step_bwd",
            "burst_attn_fill_zigzag_mask", "burst_attn_fill_contiguous_mask", "burst_attn_fill_striped_mask",
            "burst_attn_fill_block_striped_mask",
-           "burst_attn_visible_pairs", "burst_attn_tile_class", "burst_attn_visible_tile_runs", "burst_attn_mfma_probe", "burst_attn_set_bwd_chunk_rows", "burst_attn_bwd_chunk_plan", "burst_attn_status_string", "burst_attn_last_hip_error",
+           "burst_attn_visible_pairs", "burst_attn_tile_class", "burst_attn_visible_tile_runs", "burst_attn_mfma_probe", "burst_attn_set_chunk_rows", "burst_attn_chunk_plan", "burst_attn_status_string", "burst_attn_last_hip_error",
            "burst_attn_version", "burst_lm_head_workspace_bytes", "burst_lm_head_loss",
            "burst_lm_head_static_scratch_bytes", "burst_lm_head_loss_noalloc"]
 
@@ -290,15 +290,15 @@ def burst_lm_head_loss_noalloc(shp, h_last, w_head, y, loss, lse=None, d_h=None,
                                            0 if d_w is None else d_w.stride(0), int(accumulate_dw), _stream(stream)))
 
 
-def burst_attn_set_bwd_chunk_rows(rows):
-    """Rows of the streamed axis per launch of a backward kernel (diagnostics); returns the value in force."""
-    return _lib.burst_attn_set_bwd_chunk_rows(int(rows))
+def burst_attn_set_chunk_rows(rows):
+    """Rows of the streamed axis per launch of a step kernel (diagnostics); returns the value in force."""
+    return _lib.burst_attn_set_chunk_rows(int(rows))
 
 
-def burst_attn_bwd_chunk_plan(mask, query_axis, max_ranges=4096):
-    """Ranges the backward launcher cuts an axis into: list of dicts (r0, r1, nseg, seg_len, pos0, period, blk_offset)."""
+def burst_attn_chunk_plan(mask, query_axis, max_ranges=4096):
+    """Ranges the step launchers cut an axis into: list of dicts (r0, r1, nseg, seg_len, pos0, period, blk_offset)."""
     out = (C.c_int64 * (7 * max_ranges))()
-    n = _lib.burst_attn_bwd_chunk_plan(C.byref(mask), int(query_axis), max_ranges, out)
+    n = _lib.burst_attn_chunk_plan(C.byref(mask), int(query_axis), max_ranges, out)
     if n < 0:
         _check(n)
     keys = ("r0", "r1", "nseg", "seg_len", "pos0", "period", "blk_offset")

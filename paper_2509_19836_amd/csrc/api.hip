@@ -4,12 +4,20 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <atomic>
 #include <mutex>
 
 #include "../../include/burst_attn.h"
 #include "../../include/burst_attn_diag.h"
 #include "../../include/burst_lm_head.h"
 #include "kernels.hpp"
+
+namespace burst {
+// Rows of a streamed axis per launch of a step kernel (kernels.hpp: chunk_ranges); process-wide.
+static std::atomic<int> g_chunk_rows{32768};
+int chunk_rows() { return g_chunk_rows.load(); }
+void set_chunk_rows(int rows) { g_chunk_rows.store(rows < 256 ? 256 : rows); }
+}  // namespace burst
 
 using namespace burst;
 
@@ -480,17 +488,17 @@ int burst_attn_visible_tile_runs(const burst_mask_t* mask, int32_t query_axis, i
   return BURST_OK;
 }
 
-int burst_attn_set_bwd_chunk_rows(int32_t rows) {
-  burst::set_bwd_chunk_rows(rows);
+int burst_attn_set_chunk_rows(int32_t rows) {
+  burst::set_chunk_rows(rows);
   return rows < 256 ? 256 : rows;
 }
 
-int burst_attn_bwd_chunk_plan(const burst_mask_t* mask, int32_t query_axis, int32_t max_ranges, int64_t* out) {
+int burst_attn_chunk_plan(const burst_mask_t* mask, int32_t query_axis, int32_t max_ranges, int64_t* out) {
   if (!mask || !out || max_ranges < 0 || mask->q_nseg < 1 || mask->k_nseg < 1) return BURST_ERR_INVALID_ARG;
   const int64_t sq = mask->q_nseg * mask->q_seg_len, sk = mask->k_nseg * mask->k_seg_len;
   MaskDev mk;
   BURST_TRY(check_mask(mask, sq, sk, &mk));
-  return bwd_chunk_plan(mk, (int)sq, (int)sk, query_axis != 0, max_ranges, out);
+  return chunk_plan(mk, (int)sq, (int)sk, query_axis != 0, max_ranges, out);
 }
 
 int burst_attn_mfma_probe(int32_t random_operands, int32_t iterations, float* sink, int64_t* flops_out,

@@ -16,9 +16,6 @@
 //    whose A operands are the dO and Q tiles read column-wise from the LDS copies that served
 //    S and dP row-wise.  With grouped-query attention the work-group walks the query heads of its
 //    group, so dK and dV are summed over the group in registers.
-#include <atomic>
-#include <vector>
-
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -533,67 +530,6 @@ __global__ __launch_bounds__(512, 1) void step_bwd_dkdv_kernel(BwdParams p) {
   else dkdv_role<D, 1>(p, smem, b, hk, bm.tile, wave - 4);
 }
 
-// ---------------------------------------------------------------------------------------------
-// Chunked launches.  The work-groups that share an XCD's L2 (4 MiB) walk the streamed axis side by side,
-// so a tile of it is fetched from HBM about once -- as long as the walk is short enough for them to stay
-// together.  Over a walk of thousands of tiles they drift apart and each streams its own copy (at 131072-row
-// chunks the dQ kernel fetched 107 GB per launch instead of 32 GB).  A long streamed axis is therefore cut into
-// row ranges of about g_chunk_rows rows, one launch per range on the same stream, the stationary side's
-// gradient accumulating in HBM from launch to launch.  Ranges of 32768 rows cost no time (16384: 1 %, 8192: 4 %).  A range lies inside one piece of the axis or covers
-// whole pieces, so it is again a chunk the mask descriptor can express.
-static std::atomic<int> g_chunk_rows{32768};
-void set_bwd_chunk_rows(int rows) { g_chunk_rows.store(rows < 256 ? 256 : rows); }
-
-struct RowRange {
-  int r0, r1;
-};
-// Ranges that cover [0, rows) of an axis of nseg pieces of seg_len rows; one range (no chunking) when the
-// axis is short or a block mask's row blocks would be cut.
-static std::vector<RowRange> chunk_ranges(int nseg, int seg_len, int rows, int blk_rows) {
-  const int target = g_chunk_rows.load();
-  std::vector<RowRange> out;
-  const bool cuts_blocks = blk_rows > 0 && ((nseg > 1 && seg_len % blk_rows != 0) || target % blk_rows != 0);
-  if (rows <= 2 * target || cuts_blocks) {
-    out.push_back({0, rows});
-    return out;
-  }
-  if (nseg <= 1 || seg_len >= target) {   // ranges inside each piece
-    const int pieces = nseg <= 1 ? 1 : nseg, len = nseg <= 1 ? rows : seg_len;
-    for (int s = 0; s < pieces; ++s)
-      for (int a = 0; a < len; a += target) out.push_back({s * len + a, s * len + (a + target < len ? a + target : len)});
-  } else {                                // whole pieces per range
-    const int per = target / seg_len > 0 ? target / seg_len : 1;
-    for (int s = 0; s < nseg; s += per) out.push_back({s * seg_len, (s + per < nseg ? s + per : nseg) * seg_len});
-  }
-  return out;
-}
-// The mask of rows [r0, r1) of the query axis (Q_AXIS) or the key axis against the whole other axis.
-template <bool Q_AXIS>
-static MaskDev sub_mask(const MaskDev& mk, int r0, int r1) {
-  MaskDev m = mk;
-  int32_t& nseg = Q_AXIS ? m.q_nseg : m.k_nseg;
-  int32_t& seg_len = Q_AXIS ? m.q_seg_len : m.k_seg_len;
-  int32_t& pos0 = Q_AXIS ? m.q_pos0 : m.k_pos0;
-  int32_t& period = Q_AXIS ? m.q_period : m.k_period;
-  if (nseg <= 1) {
-    pos0 += r0 * m.pos_stride;
-    seg_len = r1 - r0;
-  } else {
-    const int s0 = r0 / seg_len;
-    if ((r1 - 1) / seg_len == s0) {   // inside piece s0
-      pos0 += s0 * period + (r0 - s0 * seg_len) * m.pos_stride;
-      nseg = 1;
-      period = 0;
-      seg_len = r1 - r0;
-    } else {                          // pieces s0 .. (r1 / seg_len) - 1, whole
-      pos0 += s0 * period;
-      nseg = (r1 - r0) / seg_len;
-    }
-  }
-  if (m.blk) m.blk += Q_AXIS ? (int64_t)(r0 / m.blk_q) * m.blk_pitch : (int64_t)(r0 / m.blk_k);
-  return m;
-}
-static void offset_rows(TensorDev& t, int r0) { t.ptr = (char*)t.ptr + (int64_t)r0 * t.ss * (t.is_f32 ? 4 : 2); }
 
 template <int D>
 static hipError_t launch_dq_t(BwdParams p, hipStream_t stream) {
@@ -674,7 +610,7 @@ static hipError_t launch_bwd_t(const BwdParams& p0, hipStream_t stream) {
 
 // Host view of the launcher's plan for tests: the ranges the query axis (dK/dV kernel) or the key axis (dQ
 // kernel) of a step is cut into, each with the piece description of its sub-mask and the block-mask offset.
-int bwd_chunk_plan(const MaskDev& mk, int sq, int sk, bool query_axis, int max_ranges, int64_t* out) {
+int chunk_plan(const MaskDev& mk, int sq, int sk, bool query_axis, int max_ranges, int64_t* out) {
   const std::vector<RowRange> ranges = query_axis ? chunk_ranges(mk.q_nseg, mk.q_seg_len, sq, mk.blk ? mk.blk_q : 0)
                                                   : chunk_ranges(mk.k_nseg, mk.k_seg_len, sk, mk.blk ? mk.blk_k : 0);
   int n = 0;

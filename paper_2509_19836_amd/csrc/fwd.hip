@@ -274,9 +274,30 @@ static hipError_t launch_fwd_t(FwdParams p, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// With the fused merge and no separate step result, a key axis longer than two ranges is cut into ranges, one
+// launch per range, each folding its part into the running (O, Lse): the same online-softmax merge the ring
+// applies from step to step, so the result is the step's up to rounding.  The step result itself (o_part,
+// lse_part) cannot be cut this way and is always one launch.
+template <int D>
+static hipError_t launch_fwd_chunked(const FwdParams& p0, hipStream_t stream) {
+  if (!p0.o_acc.ptr || p0.o_part.ptr) return launch_fwd_t<D>(p0, stream);
+  const std::vector<RowRange> ranges = chunk_ranges(p0.mask.k_nseg, p0.mask.k_seg_len, p0.sk, p0.mask.blk ? p0.mask.blk_k : 0);
+  if (ranges.size() == 1) return launch_fwd_t<D>(p0, stream);
+  for (const RowRange& rg : ranges) {
+    FwdParams p = p0;
+    p.mask = sub_mask<false>(p0.mask, rg.r0, rg.r1);
+    p.sk = rg.r1 - rg.r0;
+    offset_rows(p.k, rg.r0);
+    offset_rows(p.v, rg.r0);
+    hipError_t e = launch_fwd_t<D>(p, stream);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 hipError_t launch_step_fwd(const FwdParams& p, hipStream_t stream) {
-  if (p.head_dim == 128) return launch_fwd_t<128>(p, stream);
-  return launch_fwd_t<64>(p, stream);
+  if (p.head_dim == 128) return launch_fwd_chunked<128>(p, stream);
+  return launch_fwd_chunked<64>(p, stream);
 }
 
 }  // namespace burst

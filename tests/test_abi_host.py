@@ -466,7 +466,7 @@ def test_backward_chunk_plan_covers_the_axis_with_the_same_positions(lib, chunk_
     order, every range is a chunk the mask descriptor expresses (inside one piece, or whole pieces), its rows
     have the positions the step's mask gives them, and with a block mask every range starts on a block row."""
     G = 4
-    assert lib.burst_attn_set_bwd_chunk_rows(chunk_rows) == chunk_rows
+    assert lib.burst_attn_set_chunk_rows(chunk_rows) == chunk_rows
     try:
         cases = [("causal", 4 * 6000, 0), ("zigzag", 4 * 2 * 1536, 0), ("zigzag", 4 * 2 * 1100, 0), ("striped", 4 * 5000, 0),
                  ("block_striped", 4 * 4096, 512), ("block_striped", 4 * 3072, 1536), ("block_striped", 4 * 8192, 8192)]
@@ -474,7 +474,7 @@ def test_backward_chunk_plan_covers_the_axis_with_the_same_positions(lib, chunk_
             m = hp.fill_mask(lib, kind, 1, 2, G, N, 0, N_blk)
             for axis, side in ((1, "q"), (0, "k")):
                 pos = hp.mask_positions(m, side)
-                plan = lib.burst_attn_bwd_chunk_plan(m, axis)
+                plan = lib.burst_attn_chunk_plan(m, axis)
                 assert plan[0]["r0"] == 0 and plan[-1]["r1"] == pos.size, (kind, N, plan)
                 if pos.size > 2 * chunk_rows:
                     assert len(plan) > 1, (kind, N, chunk_rows)
@@ -488,12 +488,12 @@ def test_backward_chunk_plan_covers_the_axis_with_the_same_positions(lib, chunk_
         m = hp.fill_mask(lib, "zigzag", 1, 2, G, 4 * 2 * 2048)
         m.block_mask = 1 << 20   # an address the host never dereferences
         m.q_block_rows, m.k_block_rows, m.block_pitch = 256, 128, 64
-        for rg in lib.burst_attn_bwd_chunk_plan(m, 1):
+        for rg in lib.burst_attn_chunk_plan(m, 1):
             assert rg["r0"] % 256 == 0 and rg["blk_offset"] == (rg["r0"] // 256) * 64
-        for rg in lib.burst_attn_bwd_chunk_plan(m, 0):
+        for rg in lib.burst_attn_chunk_plan(m, 0):
             assert rg["r0"] % 128 == 0 and rg["blk_offset"] == rg["r0"] // 128
         m.q_block_rows = 768   # 768 does not divide the range length: one launch
-        assert len(lib.burst_attn_bwd_chunk_plan(m, 1)) == 1
-        assert len(lib.burst_attn_bwd_chunk_plan(hp.fill_mask(lib, "causal", 1, 2, G, 4 * 2 * chunk_rows), 1)) == 1
+        assert len(lib.burst_attn_chunk_plan(m, 1)) == 1
+        assert len(lib.burst_attn_chunk_plan(hp.fill_mask(lib, "causal", 1, 2, G, 4 * 2 * chunk_rows), 1)) == 1
     finally:
-        lib.burst_attn_set_bwd_chunk_rows(32768)
+        lib.burst_attn_set_chunk_rows(32768)
