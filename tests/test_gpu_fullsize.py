@@ -58,6 +58,11 @@ def _step_sampled(lib, B, n, Hq, Hkv, d, mask, scale, seed, head_scale=False, ba
     lse_part = torch.empty(B, Hq, n, **f32)
     print(f"step fwd B={B} n={n} Hq={Hq} Hkv={Hkv}", flush=True)
     lib.burst_attn_step_fwd(shp, mask, q, k, v, o_part=o_part, lse_part=lse_part)
+    # The form the benchmark times: the step folded straight into a running state (from (0, -inf) here), which
+    # the launcher cuts into key ranges at these sizes.
+    o_acc = torch.zeros(B, n, Hq, d, **f32)
+    lse_acc = torch.full((B, Hq, n), -float("inf"), **f32)
+    lib.burst_attn_step_fwd(shp, mask, q, k, v, o_acc=o_acc, lse_acc=lse_acc)
     # Backward inputs as a longer ring would deliver them: a larger, finite Lse and some D.  They derive
     # from this step's own forward result (checked against the oracle below) only to be of a realistic
     # size; the backward step is a function of whatever (Lse, D) it is given, and the oracle is handed
@@ -86,6 +91,8 @@ def _step_sampled(lib, B, n, Hq, Hkv, d, mask, scale, seed, head_scale=False, ba
         O_ref, lse_ref = oc.step_fwd(Qh[rows], Kh, Vh, scale, vis_r)
         _assert_close(to64(o_part[bi, :, head])[rows], O_ref, keys_seen, f"O head {head}")
         assert hp.lse_err(to64(lse_part[bi, head])[rows], lse_ref) <= hp.LSE_TOL
+        _assert_close(to64(o_acc[bi, :, head])[rows], O_ref, keys_seen, f"running O head {head}")
+        assert hp.lse_err(to64(lse_acc[bi, head])[rows], lse_ref) <= hp.LSE_TOL
         dQ_ref, _, _ = oc.step_bwd(Qh[rows], Kh, Vh, dOh[rows], lse_h[rows], d_h[rows], scale, vis_r)
         _assert_close(to64(dq[bi, :, head])[rows], dQ_ref, keys_seen, f"dQ head {head}")
     # whole key rows: dK / dV of a KV head collect every query head of its group
