@@ -109,17 +109,24 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void step_fwd_kernel(FwdP
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) mask_tile<true>(s[kb], mk, k0 + kb * 32, h, sk, qpos);
       }
-      float mx = s[0][0];
+      // largest score among this lane's keys of the tile (the row's other keys sit in the lane 32 away):
+      // four short chains instead of one long one
+      float mx4[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) mx4[j] = fmaxf(s[0][j], s[0][j + 4]);
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
-      mx = fmaxf(mx, half_swap(mx));
-      const float m_new = fmaxf(m_run, mx);
+        for (int v = (kb == 0 ? 8 : 0); v < 16; ++v) mx4[v & 3] = fmaxf(mx4[v & 3], s[kb][v]);
+      const float mx_own = fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3]));
       // Rescale lazily: keep a stale maximum while no row of the wave has grown by more than
-      // 2^kLazyLog2 (any common per-row offset gives the same result; fp32 has the headroom).
-      const bool grow = c * (m_new - m_run) > kLazyLog2;   // false for -inf - -inf
+      // 2^kLazyLog2 (any common per-row offset gives the same result; fp32 has the headroom).  A row has
+      // grown exactly if one of its two lanes has, and the vote runs over the whole wave, so the two halves
+      // of a row exchange their maxima only when a rescale happens: the steady state has no cross-lane
+      // traffic (the exchange goes through LDS and costs a round trip the wave cannot fill).
+      const bool grow = c * (mx_own - m_run) > kLazyLog2;   // false for -inf - -inf
       if (__any(grow)) {
+        const float m_new = fmaxf(m_run, fmaxf(mx_own, half_swap(mx_own)));
         const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(c * (m_run - m_new));
         m_run = m_new;
         l_run *= alpha;
