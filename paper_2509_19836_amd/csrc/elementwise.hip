@@ -1,5 +1,5 @@
 // HBM-bound helpers: the standalone online-softmax merge (forward algorithm),
-// D = rowsum(dO o O) (Alg. 2), and fills.  One lane moves 16 or 32 bytes per tensor; the
+// D = rowsum(dO o O) (Alg. 2), and fills.  One lane moves 8 elements (16 or 32 bytes) per tensor; the
 // lanes of one row sit next to each other in one wave, so every row is read and written as
 // whole contiguous head_dim vectors.
 #include "common.hpp"
@@ -12,25 +12,90 @@ static int grid_for(int64_t total) {
   return (int)(blocks < 256 * 32 ? blocks : 256 * 32);
 }
 
-__device__ __forceinline__ f32x4 load4(const TensorDev& t, int64_t off) {
-  if (t.is_f32) return *reinterpret_cast<const f32x4*>((const float*)t.ptr + off);
-  bf16x4 x = *reinterpret_cast<const bf16x4*>((const __bf16*)t.ptr + off);
-  return f32x4{(float)x[0], (float)x[1], (float)x[2], (float)x[3]};
+// Cursor of a 256-thread block over the "head rows" (batch, row, head) of a [batch, rows, heads, head_dim]
+// tensor, 8 elements per lane: LANES = head_dim / 8 neighbouring lanes share a head row, a block covers
+// 256 / LANES consecutive head rows per step and moves on by the whole grid.  The index is split into
+// (batch, row, head) once, with the only wide divisions of the kernel, and then advanced by adding the
+// pre-split stride with carries: these kernels move 50-100 bytes per lane and step, which a 64-bit division
+// per tensor coordinate (several hundred instructions a lane) would outweigh.
+struct HeadRowCursor {
+  int64_t left;          // head rows from this lane's one to the end (<= 0: past the end)
+  int64_t b;
+  int32_t row, hq, c;    // c: which 8 elements of the head row
+  int64_t step_b, step_total;
+  int32_t step_row, step_hq;
+  int32_t rows, heads;
+
+  __device__ __forceinline__ void init(int32_t batch, int32_t rows_, int32_t heads_, int32_t head_dim) {
+    rows = rows_;
+    heads = heads_;
+    const int lanes = head_dim / 8, per_block = 256 / lanes;
+    c = threadIdx.x % lanes;
+    const int64_t total = (int64_t)batch * rows * heads;
+    const int64_t first = (int64_t)blockIdx.x * per_block + threadIdx.x / lanes;
+    left = total - first;
+    const int64_t br = first / heads;
+    hq = (int32_t)(first - br * heads);
+    b = br / rows;
+    row = (int32_t)(br - b * rows);
+    step_total = (int64_t)gridDim.x * per_block;
+    const int64_t sbr = step_total / heads;
+    step_hq = (int32_t)(step_total - sbr * heads);
+    step_b = sbr / rows;
+    step_row = (int32_t)(sbr - step_b * rows);
+  }
+  __device__ __forceinline__ bool live() const { return left > 0; }
+  __device__ __forceinline__ void advance() {
+    left -= step_total;
+    hq += step_hq;
+    int carry = 0;
+    if (hq >= heads) {
+      hq -= heads;
+      carry = 1;
+    }
+    row += step_row + carry;
+    if (row >= rows) {   // step_row + 1 <= rows: one subtraction is enough
+      row -= rows;
+      ++b;
+    }
+    b += step_b;
+  }
+  __device__ __forceinline__ int64_t offset(const TensorDev& t) const { return b * t.sb + (int64_t)row * t.ss + hq * t.sh + c * 8; }
+  __device__ __forceinline__ int64_t offset(const RowvecDev& t) const { return b * t.sb + hq * t.sh + row; }
+};
+
+static int head_row_grid(int32_t batch, int32_t rows, int32_t heads, int32_t head_dim) {
+  const int per_block = 256 / (head_dim / 8);
+  const int64_t blocks = ((int64_t)batch * rows * heads + per_block - 1) / per_block;
+  // One step per lane up to 2^20 blocks: measured at 131072 x 32 head rows of 128, a grid capped at 8192 blocks
+  // that loops 32 times streams 4.9 TB/s, the uncapped one 5.5 (D) and 5.2 (merge).
+  constexpr int64_t kMaxBlocks = 1 << 20;
+  return (int)(blocks < kMaxBlocks ? blocks : kMaxBlocks);
+}
+
+__device__ __forceinline__ void load8(const TensorDev& t, int64_t off, f32x4& lo, f32x4& hi) {
+  if (t.is_f32) {
+    lo = *reinterpret_cast<const f32x4*>((const float*)t.ptr + off);
+    hi = *reinterpret_cast<const f32x4*>((const float*)t.ptr + off + 4);
+  } else {
+    const bf16x8 x = *reinterpret_cast<const bf16x8*>((const __bf16*)t.ptr + off);
+    lo = f32x4{(float)x[0], (float)x[1], (float)x[2], (float)x[3]};
+    hi = f32x4{(float)x[4], (float)x[5], (float)x[6], (float)x[7]};
+  }
 }
 
 __global__ __launch_bounds__(256) void lse_merge_kernel(MergeParams p) {
-  const int d4 = p.head_dim / 4;
-  const int64_t total = (int64_t)p.batch * p.sq * p.q_heads * d4;
-  for (int64_t i = blockIdx.x * 256ll + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    const int c = i % d4;
-    int64_t rest = i / d4;
-    const int hq = rest % p.q_heads;
-    rest /= p.q_heads;
-    const int row = rest % p.sq;
-    const int b = rest / p.sq;
-    float* lse_ptr = p.lse_acc.ptr + b * p.lse_acc.sb + hq * p.lse_acc.sh + row;
+  HeadRowCursor cur;
+  cur.init(p.batch, p.sq, p.q_heads, p.head_dim);
+  for (; cur.live(); cur.advance()) {
+    float* lse_ptr = p.lse_acc.ptr + cur.offset(p.lse_acc);
     const float a = *lse_ptr;
-    const float bcur = p.lse_part.ptr[b * p.lse_part.sb + hq * p.lse_part.sh + row];
+    const float bcur = p.lse_part.ptr[cur.offset(p.lse_part)];
+    const int64_t off_acc = cur.offset(p.o_acc);
+    f32x4 oa0 = *reinterpret_cast<const f32x4*>((const float*)p.o_acc.ptr + off_acc);
+    f32x4 oa1 = *reinterpret_cast<const f32x4*>((const float*)p.o_acc.ptr + off_acc + 4);
+    f32x4 op0, op1;
+    load8(p.o_part, cur.offset(p.o_part), op0, op1);
     const float mm = fmaxf(a, bcur);
     float w_old = 0.f, w_cur = 0.f, lse_new = -INFINITY;
     if (mm != -INFINITY) {
@@ -40,63 +105,51 @@ __global__ __launch_bounds__(256) void lse_merge_kernel(MergeParams p) {
       w_old = e_old / tot;
       w_cur = e_cur / tot;
     }
-    const int64_t off_acc = b * p.o_acc.sb + (int64_t)row * p.o_acc.ss + hq * p.o_acc.sh + c * 4;
-    const int64_t off_part = b * p.o_part.sb + (int64_t)row * p.o_part.ss + hq * p.o_part.sh + c * 4;
-    f32x4 oa = *reinterpret_cast<const f32x4*>((const float*)p.o_acc.ptr + off_acc);
-    f32x4 op = load4(p.o_part, off_part);
-    f32x4 out;
+    f32x4 out0, out1;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       // a weight of 0 must also silence a non-finite partner (0 * inf)
-      float x = (w_cur != 0.f ? w_cur * op[e] : 0.f) + (w_old != 0.f ? w_old * oa[e] : 0.f);
-      out[e] = x;
+      out0[e] = (w_cur != 0.f ? w_cur * op0[e] : 0.f) + (w_old != 0.f ? w_old * oa0[e] : 0.f);
+      out1[e] = (w_cur != 0.f ? w_cur * op1[e] : 0.f) + (w_old != 0.f ? w_old * oa1[e] : 0.f);
     }
-    *reinterpret_cast<f32x4*>((float*)p.o_acc.ptr + off_acc) = out;
+    *reinterpret_cast<f32x4*>((float*)p.o_acc.ptr + off_acc) = out0;
+    *reinterpret_cast<f32x4*>((float*)p.o_acc.ptr + off_acc + 4) = out1;
     if (p.o_out.ptr) {
-      const int64_t off_out = b * p.o_out.sb + (int64_t)row * p.o_out.ss + hq * p.o_out.sh + c * 4;
-      bf16x4 y = {(__bf16)out[0], (__bf16)out[1], (__bf16)out[2], (__bf16)out[3]};
-      *reinterpret_cast<bf16x4*>((__bf16*)p.o_out.ptr + off_out) = y;
+      const bf16x8 y = {(__bf16)out0[0], (__bf16)out0[1], (__bf16)out0[2], (__bf16)out0[3],
+                        (__bf16)out1[0], (__bf16)out1[1], (__bf16)out1[2], (__bf16)out1[3]};
+      *reinterpret_cast<bf16x8*>((__bf16*)p.o_out.ptr + cur.offset(p.o_out)) = y;
     }
-    // all lanes of this row are in this wave and have already loaded lse_acc above
-    if (c == 0) *lse_ptr = lse_new;
+    // the lanes of this head row sit in one wave and have all loaded lse_acc above
+    if (cur.c == 0) *lse_ptr = lse_new;
   }
 }
 
 hipError_t launch_lse_merge(const MergeParams& p, hipStream_t stream) {
-  const int64_t total = (int64_t)p.batch * p.sq * p.q_heads * (p.head_dim / 4);
-  const int grid = grid_for(total);
+  if ((int64_t)p.batch * p.sq * p.q_heads == 0) return hipSuccess;
+  const int grid = head_row_grid(p.batch, p.sq, p.q_heads, p.head_dim);
   hipLaunchKernelGGL(lse_merge_kernel, dim3(grid), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 
 __global__ __launch_bounds__(256) void preprocess_bwd_kernel(PreParams p) {
-  const int d8 = p.head_dim / 8;   // lanes per row: 8 (D=64) or 16 (D=128)
-  const int64_t total = (int64_t)p.batch * p.sq * p.q_heads * d8;
-  const int64_t padded = (total + 255) / 256 * 256;   // whole waves run the shuffles
-  for (int64_t i = blockIdx.x * 256ll + threadIdx.x; i < padded; i += (int64_t)gridDim.x * 256) {
-    const bool live = i < total;
-    const int64_t ii = live ? i : total - 1;
-    const int c = ii % d8;
-    int64_t rest = ii / d8;
-    const int hq = rest % p.q_heads;
-    rest /= p.q_heads;
-    const int row = rest % p.sq;
-    const int b = rest / p.sq;
-    const int64_t off_o = b * p.o.sb + (int64_t)row * p.o.ss + hq * p.o.sh + c * 8;
-    const int64_t off_do = b * p.d_o.sb + (int64_t)row * p.d_o.ss + hq * p.d_o.sh + c * 8;
-    f32x4 o0 = load4(p.o, off_o), o1 = load4(p.o, off_o + 4);
-    f32x4 g0 = load4(p.d_o, off_do), g1 = load4(p.d_o, off_do + 4);
+  const int lanes = p.head_dim / 8;   // lanes per head row: 8 (D=64) or 16 (D=128); a head row never straddles a wave
+  HeadRowCursor cur;
+  cur.init(p.batch, p.sq, p.q_heads, p.head_dim);
+  for (; cur.live(); cur.advance()) {   // the lanes of a head row leave the loop together
+    f32x4 o0, o1, g0, g1;
+    load8(p.o, cur.offset(p.o), o0, o1);
+    load8(p.d_o, cur.offset(p.d_o), g0, g1);
     float acc = 0.f;
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc += o0[e] * g0[e] + o1[e] * g1[e];
-    for (int s = 1; s < d8; s <<= 1) acc += __shfl_xor(acc, s, 64);
-    if (live && c == 0) p.d.ptr[b * p.d.sb + hq * p.d.sh + row] = acc;
+    for (int s_ = 1; s_ < lanes; s_ <<= 1) acc += __shfl_xor(acc, s_, 64);
+    if (cur.c == 0) p.d.ptr[cur.offset(p.d)] = acc;
   }
 }
 
 hipError_t launch_preprocess_bwd(const PreParams& p, hipStream_t stream) {
-  const int64_t total = (int64_t)p.batch * p.sq * p.q_heads * (p.head_dim / 8);
-  const int grid = grid_for(total);
+  if ((int64_t)p.batch * p.sq * p.q_heads == 0) return hipSuccess;
+  const int grid = head_row_grid(p.batch, p.sq, p.q_heads, p.head_dim);
   hipLaunchKernelGGL(preprocess_bwd_kernel, dim3(grid), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
