@@ -29,8 +29,8 @@ PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flo
 # process, so the figure is the profiled one: it is reported with the profile it came from and its date,
 # and only for the workload that was profiled.
 PROFILED_TRAFFIC = {
-    2: {"bytes": 1.976e9, "profile": "profiles/bench_config2_pmc_hbm_traffic.md", "taken": "with the kernels and launch plan as committed (pipelined dK/dV, 32768-row ranges)"},
-    5: {"bytes": 2.167e11, "profile": "profiles/bench_config5_pmc_hbm_traffic.md", "taken": "with the kernels and launch plan as committed (pipelined dK/dV, 32768-row ranges)"},
+    2: {"bytes": 1.984e9, "profile": "profiles/bench_config2_pmc_hbm_traffic.md", "taken": "with the kernels and launch plan as committed (pipelined dK/dV, 32768-row ranges)"},
+    5: {"bytes": 1.961e11, "profile": "profiles/bench_config5_pmc_hbm_traffic.md", "taken": "with the kernels and launch plan as committed (pipelined dK/dV, 32768-row ranges)"},
 }
 # --lm-head, default shape: bytes per call over all its launches (profiles/bench_lm_head_kernel_trace_and_counters.md)
 PROFILED_LM_HEAD_TRAFFIC_BYTES = 2.73e10
